@@ -1,0 +1,211 @@
+"""Pins for the numpy oracle: values the paper prints, closed forms, exact brute force,
+special cases that reduce to textbook routines.  CPU only."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import hlq_oracle as O
+from paper_2510_19482_amd import synth
+
+
+def tiny(K, N, q, G, M, seed):
+    codes, S, Z = synth.make_weight(K, N, q, G, "tiny", seed)
+    X = synth.make_x(M, K, "tiny", seed)
+    return X, codes, S, Z
+
+
+# ----------------------------------------------------------------- printed in the paper
+def test_bitplane_worked_example(golden):
+    rows = {r[0]: [int(v) for v in r[1:]] for r in golden("bitplane_example.txt")}
+    codes = np.array(rows["codes"], dtype=np.uint8)
+    planes = O.bit_planes(codes, 4)
+    for j in range(4):
+        assert planes[j].tolist() == rows[f"plane{j}"], j
+    assert O.codes_from_planes(planes).tolist() == rows["codes"]
+
+
+def test_bits_per_weight_table1(golden):
+    for q, G, kind, printed in golden("bpw_table1.txt"):
+        ours = O.bits_per_weight(int(q), int(G), uniform=(kind == "uniform"))
+        # two printed decimals, truncated or rounded
+        assert abs(ours - float(printed)) < 0.0051, (q, G, kind, ours)
+
+
+def _layer_shapes(model):
+    return synth.LLAMA31_8B_LAYER if model == "llama3.1-8b" else synth.LLAMA31_70B_LAYER
+
+
+def test_packed_bytes_matches_bpw_and_model_sizes(golden):
+    # closed form == K*N*BPW/8 exactly
+    for q, G in [(2, 128), (2, 64), (3, 128), (4, 128), (1, 32)]:
+        K, N = 1024, 256
+        assert O.packed_bytes(K, N, q, G) * 8 == K * N * O.bits_per_weight(q, G)
+    # whole-model sizes of Table 3: all decoder layers in HLQ, embedding + LM head fp16,
+    # norm vectors fp16
+    dims = {"llama3.1-8b": (32, 4096, 128256), "llama3.1-70b": (80, 8192, 128256)}
+    for model, q, uni_gb, hlq_gb in golden("model_size_table3.txt"):
+        q = int(q)
+        layers, hidden, vocab = dims[model]
+        shapes = _layer_shapes(model)
+        fp16_rest = 2 * vocab * hidden * 2 + (2 * layers + 1) * hidden * 2
+        hlq = layers * sum(O.packed_bytes(s.K, s.N, q, 128) for s in shapes) + fp16_rest
+        nweights = layers * sum(s.K * s.N for s in shapes)
+        uni = nweights * O.bits_per_weight(q, 128, uniform=True) / 8 + fp16_rest
+        # printed to 3 (8B) or 2 (70B) decimals, truncated or rounded
+        tol = 0.0011 if model == "llama3.1-8b" else 0.011
+        assert abs(hlq / 2**30 - float(hlq_gb)) < tol, (model, q, hlq / 2**30)
+        assert abs(uni / 2**30 - float(uni_gb)) < tol, (model, q, uni / 2**30)
+
+
+def test_block_parameter_counts(golden):
+    rows = {r[0]: float(r[1]) for r in golden("trainable_params.txt")}
+    nweights = sum(s.K * s.N for s in synth.LLAMA31_8B_LAYER)
+    assert nweights == 218_103_808
+    assert round(nweights / 1e6) == rows["block_weights"]
+    q, G = 2, 128
+    n_sz = sum((q + 1) * (s.K // G) * s.N for s in synth.LLAMA31_8B_LAYER)
+    assert round(n_sz / 1e6) == rows["elutq_trainable"]
+    # and the metadata byte count of packed_bytes is exactly those fp16 values
+    meta = sum(O.packed_bytes(s.K, s.N, q, G) - s.K * s.N * q // 8 for s in synth.LLAMA31_8B_LAYER)
+    assert meta == 2 * n_sz
+
+
+# --------------------------------------------------------------------- exact brute force
+@pytest.mark.parametrize("K,N,q,G,M", [(8, 3, 1, 4, 1), (16, 4, 2, 8, 2), (16, 2, 3, 4, 1),
+                                       (8, 2, 4, 8, 2)])
+def test_dequant_reference_vs_exact_rationals(K, N, q, G, M):
+    X, codes, S, Z = tiny(K, N, q, G, M, 1)
+    exact = O.gemm_exact(X, codes, S, Z, q, G)
+    for fn in (O.gemm_dequant, O.gemm_naive, O.gemm_lut, O.gemm_lut_mirror):
+        Y = fn(X, codes, S, Z, q, G)
+        for m in range(M):
+            for n in range(N):
+                e = exact[m][n]
+                assert abs(Fraction(float(Y[m, n])) - e) <= abs(e) * Fraction(1, 10**13) + Fraction(1, 10**15), fn.__name__
+
+
+def test_hand_computed_case():
+    # K=4, one group, q=2: codes (3,0,1,2) -> w = (s0+s1+z, z, s0+z, s1+z)
+    codes = np.array([[3], [0], [1], [2]], dtype=np.uint8)
+    S = np.array([[[0.5]], [[0.25]]], dtype=np.float16)      # s0=0.5, s1=0.25
+    Z = np.array([[-0.125]], dtype=np.float16)
+    X = np.array([[1.0, 2.0, 4.0, 8.0]], dtype=np.float16)
+    expect = 1 * 0.625 + 2 * (-0.125) + 4 * 0.375 + 8 * 0.125
+    for fn in (O.gemm_dequant, O.gemm_naive, O.gemm_lut, O.gemm_lut_mirror):
+        assert fn(X, codes, S, Z, 2, 4)[0, 0] == expect, fn.__name__
+
+
+# ------------------------------------------------------------------------ special cases
+def test_uniform_special_case_is_integer_dequant():
+    # Alg. 1 initialisation s = [D, 2D, 4D, ...]: HLQ collapses to uniform D*code + z
+    K, N, q, G, M = 256, 24, 3, 64, 3
+    X, codes, _, Z = tiny(K, N, q, G, M, 2)
+    delta = synth.make_scales(K, N, 1, G, "delta")[0].astype(np.float64)   # [K/G, N]
+    S = np.stack([delta * (1 << j) for j in range(q)]).astype(np.float16)
+    assert np.array_equal(S.astype(np.float64), np.stack([delta * (1 << j) for j in range(q)]))
+    W = np.repeat(delta, G, axis=0) * codes.astype(np.float64) + np.repeat(Z.astype(np.float64), G, axis=0)
+    ref = X.astype(np.float64) @ W
+    for fn in (O.gemm_dequant, O.gemm_lut, O.gemm_lut_mirror):
+        np.testing.assert_allclose(fn(X, codes, S, Z, q, G), ref, rtol=1e-12, atol=1e-12)
+
+
+def test_one_hot_reads_back_every_weight():
+    K, N, q, G = 64, 8, 3, 16
+    _, codes, S, Z = tiny(K, N, q, G, 1, 3)
+    W = O.dequantize(codes, S, Z, q, G)
+    X = np.eye(K, dtype=np.float16)
+    for fn in (O.gemm_dequant, O.gemm_lut, O.gemm_lut_mirror):
+        np.testing.assert_allclose(fn(X, codes, S, Z, q, G), W, rtol=0, atol=1e-15)
+    # and W itself, element by element, from the definition
+    for k in (0, 17, 63):
+        for n in (0, 5):
+            w = float(Z[k // G, n]) + sum(float(S[j, k // G, n]) for j in range(q) if (codes[k, n] >> j) & 1)
+            assert W[k, n] == w
+
+
+def test_all_zero_and_all_one_planes():
+    K, N, q, G, M = 128, 16, 2, 32, 2
+    X, _, S, Z = tiny(K, N, q, G, M, 4)
+    xs = X.astype(np.float64).reshape(M, K // G, G).sum(axis=2)          # [M, K/G]
+    zero = np.zeros((K, N), dtype=np.uint8)
+    ones = np.full((K, N), (1 << q) - 1, dtype=np.uint8)
+    for fn in (O.gemm_dequant, O.gemm_lut, O.gemm_lut_mirror):
+        np.testing.assert_allclose(fn(X, zero, S, Z, q, G), xs @ Z.astype(np.float64), rtol=1e-12, atol=1e-12)
+        tot = Z.astype(np.float64) + S.astype(np.float64).sum(axis=0)
+        np.testing.assert_allclose(fn(X, ones, S, Z, q, G), xs @ tot, rtol=1e-12, atol=1e-12)
+
+
+def test_single_plane_unit_scale_is_subset_sum():
+    K, N, G = 32, 8, 8
+    X, codes, _, _ = tiny(K, N, 1, G, 1, 5)
+    S = np.ones((1, K // G, N), dtype=np.float16)
+    Z = np.zeros((K // G, N), dtype=np.float16)
+    for n in range(N):
+        expect = sum(float(X[0, k]) for k in range(K) if codes[k, n] & 1)
+        for fn in (O.gemm_dequant, O.gemm_lut, O.gemm_lut_mirror):
+            assert abs(fn(X, codes, S, Z, 1, G)[0, n] - expect) < 1e-12
+
+
+def test_linearity_and_plane_additivity():
+    K, N, q, G = 64, 8, 3, 16
+    X, codes, S, Z = tiny(K, N, q, G, 2, 6)
+    Y = O.gemm_dequant(X, codes, S, Z, q, G)
+    # rows with exactly representable combinations: x0 + 2*x1
+    Xc = (X[0:1].astype(np.float64) + 2 * X[1:2].astype(np.float64))
+    Yc = Xc @ O.dequantize(codes, S, Z, q, G)
+    np.testing.assert_allclose(Yc[0], Y[0] + 2 * Y[1], rtol=1e-12, atol=1e-12)
+    # additivity over planes: sum of single-plane problems (zero offset) + offset term
+    zero_z = np.zeros_like(Z)
+    acc = O.gemm_dequant(X, np.zeros_like(codes), S[:1], Z, 1, G)
+    for j in range(q):
+        acc = acc + O.gemm_dequant(X, (codes >> j) & 1, S[j:j + 1], zero_z, 1, G)
+    np.testing.assert_allclose(acc, Y, rtol=1e-12, atol=1e-12)
+
+
+# --------------------------------------------------------- LUT identity at mid-size shapes
+@pytest.mark.parametrize("q,G", [(2, 128), (3, 64), (4, 32)])
+def test_lut_equals_dequant(q, G):
+    K, N, M = 512, 96, 2
+    codes, S, Z = synth.make_weight(K, N, q, G, "lutid")
+    X = synth.make_x(M, K, "lutid", outliers=True)
+    ref = O.gemm_dequant(X, codes, S, Z, q, G)
+    scale = np.abs(ref).max()
+    assert np.abs(O.gemm_lut(X, codes, S, Z, q, G) - ref).max() <= 1e-12 * scale
+    assert np.abs(O.gemm_lut_mirror(X, codes, S, Z, q, G) - ref).max() <= 1e-12 * scale
+
+
+def test_mirror_tables_antisymmetric_and_params():
+    x = synth.make_x(1, 64, "mirror")[0]
+    T = O.build_tables(x)                       # 16-entry {0,1} tables
+    Tm = O.build_tables_mirror(x)               # 8-entry +-1 half tables
+    tot = T[:, 15]
+    full = 2 * T - tot[:, None]                 # +-1 table from the {0,1} one
+    np.testing.assert_allclose(full[:, :8], Tm, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(full[:, 8:], -full[:, 7::-1], rtol=0, atol=1e-12)
+    S = np.array([[[0.5]], [[0.25]]], dtype=np.float16)
+    Z = np.array([[0.125]], dtype=np.float16)
+    s_hat, z_hat = O.mirror_params(S, Z)
+    assert s_hat.ravel().tolist() == [0.25, 0.125] and z_hat.item() == 0.5
+
+
+# --------------------------------------------------- planted mistakes must trip the pins
+def test_pins_catch_planted_mistakes():
+    K, N, q, G = 64, 8, 3, 16
+    X, codes, S, Z = tiny(K, N, q, G, 1, 7)
+    good = O.gemm_dequant(X, codes, S, Z, q, G)
+    scale = np.abs(good).max()
+    mistakes = {
+        "planes reversed": O.gemm_dequant(X, codes, S[::-1].copy(), Z, q, G),
+        "offset dropped": O.gemm_dequant(X, codes, S, np.zeros_like(Z), q, G),
+        "group index shifted": O.gemm_dequant(X, codes, np.roll(S, 1, axis=1), np.roll(Z, 1, axis=0), q, G),
+        "k reversed": O.gemm_dequant(X[:, ::-1].copy(), codes, S, Z, q, G),
+    }
+    for name, bad in mistakes.items():
+        assert np.abs(bad - good).max() > 1e-3 * scale, name
+
+
+def test_row_rel_err():
+    ref = np.array([[1.0, -4.0], [0.5, 0.25]])
+    y = ref + np.array([[0.004, 0.0], [0.0, 0.001]])
+    np.testing.assert_allclose(O.row_rel_err(y, ref), [0.001, 0.002])
