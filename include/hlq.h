@@ -1,0 +1,108 @@
+/* hlq.h -- C ABI of libhlq: bit-serial LUT GEMV/GEMM over HLQ weights on MI355X (gfx950).
+ *
+ * The operation (paper: Sec. 2 "Bit-Serial LUT-Based GEMM", App. B, App. D; format: Eq. 3):
+ *
+ *     W^[k,n] = sum_{j<q} s_j[k/G, n] * b_j[k,n] + z[k/G, n],   b_j in {0,1}      (Eq. 3)
+ *     Y[m,n]  = sum_k X[m,k] * W^[k,n]
+ *
+ * computed without reconstructing W^: activations are taken four at a time, each group
+ * of four gets a 16-entry table of the partial sums sum_r bit_r(i) * x[4t+r], and every
+ * 4-bit slice of every bit-plane indexes that table; looked-up entries are added in
+ * fp32, multiplied once per (plane, quant group) by s_j, and z enters as
+ * z * (sum of the group's activations).
+ *
+ * Conventions
+ *   - Every pointer below is a DEVICE pointer unless it is marked "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Calls are asynchronous on `stream`; the library never allocates, frees or
+ *     synchronises, and keeps no pointer after a call returns.  All buffers stay owned by
+ *     the caller and must stay alive until the stream has run the call.
+ *   - Argument errors are found on the host before anything is launched and are reported
+ *     through the return code; nothing aborts or throws across this boundary.
+ *   - Supported descriptors: 1 <= q <= 4, G in {32, 64, 128, 256}, K % 128 == 0,
+ *     K % G == 0, N % 8 == 0, K, N >= 1, layout == hlq_layout_version().
+ */
+#ifndef HLQ_H
+#define HLQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    HLQ_OK = 0,
+    HLQ_ERR_NULL = 1,             /* a required pointer is NULL                              */
+    HLQ_ERR_BAD_DESC = 2,         /* q, G, K, N or layout outside the supported set          */
+    HLQ_ERR_UNSUPPORTED = 3,      /* valid request this build has no kernel for              */
+    HLQ_ERR_BUFFER_TOO_SMALL = 4, /* packed / workspace buffer smaller than required         */
+    HLQ_ERR_BAD_STRIDE = 5,       /* ldx < K, ldy < N, or M < 0                              */
+    HLQ_ERR_HIP = 6               /* the HIP runtime refused a launch                        */
+} hlq_status;
+
+#define HLQ_API __attribute__((visibility("default")))
+
+typedef enum { HLQ_OUT_F16 = 0, HLQ_OUT_F32 = 1 } hlq_out_dtype;
+
+/* One HLQ weight matrix W[K, N] (K = input features, N = output columns; the paper's
+ * W in R^{n x k} of Alg. 1 with n = out-channels and groups along k is the same thing):
+ * q bit-planes, quantisation groups of G consecutive k.  `layout` is the version tag
+ * of the packed byte layout and must equal hlq_layout_version(). */
+typedef struct {
+    int32_t K, N, q, G;
+    uint32_t layout;
+} hlq_desc;
+
+/* Static, NUL-terminated description of a status code (never NULL). */
+HLQ_API const char *hlq_status_string(hlq_status s);
+
+/* Version tag of the packed layout this library reads and writes. */
+HLQ_API uint32_t hlq_layout_version(void);
+
+/* Size of the packed weight blob.  Equals K*N*(q/8 + 2*(q+1)/G) bytes: q one-bit planes
+ * plus q fp16 scales and one fp16 zero per (group, column) -- the bits-per-weight
+ * accounting of Table 1 (q + 16(q+1)/G).  `bits` / `meta` (optional, host) receive the
+ * two parts; the planes come first in the blob, the scales/zeros start at byte `bits`.
+ * Host-only, no GPU needed. */
+HLQ_API hlq_status hlq_packed_bytes(const hlq_desc *d, size_t *total, size_t *bits, size_t *meta);
+
+/* Bytes of caller-provided workspace hlq_lut_gemv / hlq_lut_gemm need for M rows (host-only).
+ * The workspace holds split-K partial sums; its contents are scratch between calls.
+ * Two calls that may run concurrently need separate workspaces. */
+HLQ_API hlq_status hlq_workspace_bytes(const hlq_desc *d, int64_t M, size_t *bytes);
+
+/* Offline step of App. B ("decomposed into q single-bit matrices offline") and of
+ * App. D, Weight-Rearrange: split codes into bit-planes and store them so the runtime
+ * kernel reads contiguous 128-bit words along the output-column dimension.
+ *   codes  u8   [K, N] row-major, bit j of codes[k,n] = plane j (bits >= q must be 0)
+ *   scales fp16 [q, K/G, N]  (raw IEEE binary16 bits)
+ *   zeros  fp16 [K/G, N]
+ *   packed out, packed_bytes >= hlq_packed_bytes().  Integer work only; bijective. */
+HLQ_API hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint16_t *scales,
+                    const uint16_t *zeros, void *packed, size_t packed_bytes, void *stream);
+
+/* Exact inverse of hlq_pack (any of codes / scales / zeros may be NULL to skip it). */
+HLQ_API hlq_status hlq_unpack(const hlq_desc *d, const void *packed, uint8_t *codes,
+                      uint16_t *scales, uint16_t *zeros, void *stream);
+
+/* y[N] = x[K] @ W^  (M = 1 decode; Sec. 2 / App. B procedure).
+ *   x fp16 [K]; y fp16 or fp32 [N] per `out`, overwritten (beta = 0), fp16 by
+ *   round-to-nearest-even from the fp32 accumulator.
+ *   ws / ws_bytes: workspace of at least hlq_workspace_bytes(d, 1). */
+HLQ_API hlq_status hlq_lut_gemv(const hlq_desc *d, const void *packed, const uint16_t *x, void *y,
+                        hlq_out_dtype out, void *ws, size_t ws_bytes, void *stream);
+
+/* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded
+ * weight words shared by all rows).  X row-major with leading dimension ldx >= K (in
+ * elements), Y row-major with ldy >= N.  M = 0 is a no-op.
+ *   ws / ws_bytes: workspace of at least hlq_workspace_bytes(d, M). */
+HLQ_API hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uint16_t *X, int64_t M,
+                        int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
+                        size_t ws_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HLQ_H */

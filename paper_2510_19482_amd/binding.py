@@ -1,0 +1,155 @@
+"""Thin ctypes binding over libhlq.so: argument marshalling only.
+
+Every step of the path (pack, tables, lookups, scaling, reduction) runs inside the HIP
+library; torch is used for device memory and the current stream.  There is no fallback: if
+the library has not been built, importing this module raises."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libhlq.so")
+
+HLQ_OK = 0
+HLQ_OUT_F16 = 0
+HLQ_OUT_F32 = 1
+
+
+class HlqDesc(ctypes.Structure):
+    _fields_ = [("K", ctypes.c_int32), ("N", ctypes.c_int32), ("q", ctypes.c_int32),
+                ("G", ctypes.c_int32), ("layout", ctypes.c_uint32)]
+
+
+class HlqError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        super().__init__(f"{fn}: {status_string(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2510_19482_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i64, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64, ctypes.c_uint32
+    dp = ctypes.POINTER(HlqDesc)
+    szp = ctypes.POINTER(ctypes.c_size_t)
+    lib.hlq_status_string.restype = ctypes.c_char_p
+    lib.hlq_status_string.argtypes = [ctypes.c_int]
+    lib.hlq_layout_version.restype = u32
+    lib.hlq_layout_version.argtypes = []
+    lib.hlq_packed_bytes.restype = ctypes.c_int
+    lib.hlq_packed_bytes.argtypes = [dp, szp, szp, szp]
+    lib.hlq_workspace_bytes.restype = ctypes.c_int
+    lib.hlq_workspace_bytes.argtypes = [dp, i64, szp]
+    lib.hlq_pack.restype = ctypes.c_int
+    lib.hlq_pack.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+    lib.hlq_unpack.restype = ctypes.c_int
+    lib.hlq_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
+    lib.hlq_lut_gemv.restype = ctypes.c_int
+    lib.hlq_lut_gemv.argtypes = [dp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
+    lib.hlq_lut_gemm.restype = ctypes.c_int
+    lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.hlq_status_string(int(status)).decode()
+
+
+def layout_version() -> int:
+    return int(lib.hlq_layout_version())
+
+
+def make_desc(K: int, N: int, q: int, G: int, layout: int | None = None) -> HlqDesc:
+    return HlqDesc(K, N, q, G, layout_version() if layout is None else layout)
+
+
+def _check(fn: str, status: int) -> None:
+    if status != HLQ_OK:
+        raise HlqError(fn, status)
+
+
+def packed_bytes(desc: HlqDesc):
+    """(total, bits, meta) byte counts of the packed blob."""
+    t, b, m = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    _check("hlq_packed_bytes", lib.hlq_packed_bytes(ctypes.byref(desc), ctypes.byref(t), ctypes.byref(b), ctypes.byref(m)))
+    return t.value, b.value, m.value
+
+
+def workspace_bytes(desc: HlqDesc, M: int) -> int:
+    w = ctypes.c_size_t()
+    _check("hlq_workspace_bytes", lib.hlq_workspace_bytes(ctypes.byref(desc), M, ctypes.byref(w)))
+    return w.value
+
+
+# ---- torch-facing helpers (device tensors in, device tensors out) -------------------------
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return int(s.cuda_stream)
+
+
+def _ptr(t) -> int:
+    return 0 if t is None else int(t.data_ptr())
+
+
+def hlq_pack(desc: HlqDesc, codes, scales, zeros, packed=None, stream=None):
+    """codes u8 [K,N], scales fp16 [q,K/G,N], zeros fp16 [K/G,N] (cuda tensors) -> packed u8 blob."""
+    import torch
+    total, _, _ = packed_bytes(desc)
+    if packed is None:
+        packed = torch.empty(total, dtype=torch.uint8, device=codes.device)
+    _check("hlq_pack", lib.hlq_pack(ctypes.byref(desc), _ptr(codes), _ptr(scales), _ptr(zeros),
+                                    _ptr(packed), packed.numel() * packed.element_size(), _stream_ptr(stream)))
+    return packed
+
+
+def hlq_unpack(desc: HlqDesc, packed, stream=None):
+    import torch
+    K, N, q, G = desc.K, desc.N, desc.q, desc.G
+    codes = torch.empty((K, N), dtype=torch.uint8, device=packed.device)
+    scales = torch.empty((q, K // G, N), dtype=torch.float16, device=packed.device)
+    zeros = torch.empty((K // G, N), dtype=torch.float16, device=packed.device)
+    _check("hlq_unpack", lib.hlq_unpack(ctypes.byref(desc), _ptr(packed), _ptr(codes), _ptr(scales),
+                                        _ptr(zeros), _stream_ptr(stream)))
+    return codes, scales, zeros
+
+
+def alloc_workspace(desc: HlqDesc, M: int, device="cuda"):
+    import torch
+    return torch.empty(max(workspace_bytes(desc, M), 256), dtype=torch.uint8, device=device)
+
+
+def hlq_lut_gemv(desc: HlqDesc, packed, x, y=None, out_f32: bool = False, ws=None, stream=None):
+    """y[N] = x[K] @ W^ ; x fp16 cuda tensor."""
+    import torch
+    if y is None:
+        y = torch.empty(desc.N, dtype=torch.float32 if out_f32 else torch.float16, device=x.device)
+    if ws is None:
+        ws = alloc_workspace(desc, 1, x.device)
+    _check("hlq_lut_gemv", lib.hlq_lut_gemv(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(y),
+                                            HLQ_OUT_F32 if out_f32 else HLQ_OUT_F16, _ptr(ws), ws.numel(),
+                                            _stream_ptr(stream)))
+    return y
+
+
+def hlq_lut_gemm(desc: HlqDesc, packed, X, Y=None, out_f32: bool = False, ws=None, stream=None):
+    """Y[M,N] = X[M,K] @ W^ ; X fp16 cuda tensor, row-major (stride(1) == 1)."""
+    import torch
+    M = X.shape[0]
+    if Y is None:
+        Y = torch.empty((M, desc.N), dtype=torch.float32 if out_f32 else torch.float16, device=X.device)
+    if ws is None:
+        ws = alloc_workspace(desc, M, X.device)
+    ldx = X.stride(0) if M > 1 else max(X.stride(0), desc.K)
+    ldy = Y.stride(0) if M > 1 else max(Y.stride(0), desc.N)
+    _check("hlq_lut_gemm", lib.hlq_lut_gemm(ctypes.byref(desc), _ptr(packed), _ptr(X), M, ldx, _ptr(Y), ldy,
+                                            HLQ_OUT_F32 if out_f32 else HLQ_OUT_F16, _ptr(ws), ws.numel(),
+                                            _stream_ptr(stream)))
+    return Y

@@ -1,0 +1,236 @@
+// hlq_lut_gemm: M > 1 bit-serial LUT GEMM (Sec. 2 "Bit-Serial LUT-Based GEMM", App. B),
+// table-lookup formulation with one table set per activation row.
+//
+// A workgroup owns 256 adjacent columns, MB rows and a slice of K that it walks in steps of
+// U = 2 chunks (256 k).  Table entries of the MB rows are interleaved, T[t][i][r], so one LDS
+// read of MB floats serves all rows for a decoded 4-bit slice: the weight words are loaded
+// and decoded once per step and shared by the rows, as in the batched reading of App. B.
+#include "hlq_internal.h"
+
+namespace {
+
+__device__ __forceinline__ float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+__device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_f32)
+{
+    if (out_f32) ((float *)y)[idx] = v;
+    else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
+}
+
+template <int MB> struct RowVec;
+template <> struct RowVec<1> { float v[1]; };
+template <> struct RowVec<2> { float v[2]; };
+template <> struct RowVec<4> { float v[4]; };
+
+template <int Q, int G, int MB>
+__global__ void __launch_bounds__(256)
+hlq_gemm_lut_kernel(const uint4 *__restrict__ bits, const uint16_t *__restrict__ meta,
+                    const uint16_t *__restrict__ X, long ldx, int M, void *__restrict__ Y, long ldy,
+                    float *__restrict__ ws, int N, int nchunks, int chunks_per_slice, int nslices,
+                    int out_f32)
+{
+    constexpr int U = 2;
+    constexpr int GS = G < 128 ? G : 128;
+    constexpr int SEG = 128 / GS;
+    constexpr int TPS = GS / 4;
+    constexpr int NT = 32 * U;              // tables per step
+    static_assert(NT * MB <= 256, "one table-build item per lane");
+    __shared__ __attribute__((aligned(16))) float T[NT * 16 * MB];
+    __shared__ float XS[U * SEG * MB];
+
+    const int tid = threadIdx.x;
+    const int n = blockIdx.x * 256 + tid;
+    const bool col_ok = n < N;
+    const int m0 = blockIdx.z * MB;
+    const int cbeg = blockIdx.y * chunks_per_slice;
+    const int cend = min(cbeg + chunks_per_slice, nchunks);
+
+    float acc[MB];
+#pragma unroll
+    for (int r = 0; r < MB; ++r) acc[r] = 0.f;
+
+    for (int c0 = cbeg; c0 < cend; c0 += U) {
+        uint4 w[U][Q];
+        uint16_t mt[U][SEG][Q + 1];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u;
+            const bool ok = col_ok && c < cend;
+#pragma unroll
+            for (int j = 0; j < Q; ++j)
+                w[u][j] = ok ? bits[((size_t)j * nchunks + c) * N + n] : make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+            for (int s = 0; s < SEG; ++s) {
+                const int g = (G >= 128) ? (c * 128) / G : c * SEG + s;
+#pragma unroll
+                for (int r = 0; r <= Q; ++r)
+                    mt[u][s][r] = ok ? meta[((size_t)g * (Q + 1) + r) * N + n] : (uint16_t)0;
+            }
+        }
+
+        __syncthreads();   // readers of the previous step's tables are done
+        if (tid < NT * MB) {
+            const int r = tid / NT, tl = tid % NT;   // a wavefront builds one row's 64 tables
+            const int k = c0 * 128 + 4 * tl;
+            const int m = m0 + r;
+            float xv[4] = {0.f, 0.f, 0.f, 0.f};
+            if (m < M && k < cend * 128) {
+                const uint2 raw = *(const uint2 *)(X + (size_t)m * ldx + k);
+                xv[0] = h2f((uint16_t)(raw.x & 0xffffu));
+                xv[1] = h2f((uint16_t)(raw.x >> 16));
+                xv[2] = h2f((uint16_t)(raw.y & 0xffffu));
+                xv[3] = h2f((uint16_t)(raw.y >> 16));
+            }
+            float e[16];
+            e[0] = 0.f;
+#pragma unroll
+            for (int i = 1; i < 16; ++i) e[i] = e[i & (i - 1)] + xv[__builtin_ctz(i)];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) T[(tl * 16 + i) * MB + r] = e[i];
+            float tot = e[15];
+#pragma unroll
+            for (int off = TPS / 2; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+            if (tl % TPS == 0) XS[(tl / TPS) * MB + r] = tot;
+        }
+        __syncthreads();
+
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+#pragma unroll
+            for (int s = 0; s < SEG; ++s) {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t wd[4] = {w[u][j].x, w[u][j].y, w[u][j].z, w[u][j].w};
+                    float p[MB];
+#pragma unroll
+                    for (int r = 0; r < MB; ++r) p[r] = 0.f;
+#pragma unroll
+                    for (int tt = 0; tt < TPS; ++tt) {
+                        const int t = s * TPS + tt;
+                        const uint32_t idx = (wd[t >> 3] >> (4 * (t & 7))) & 15u;
+                        const RowVec<MB> e = *(const RowVec<MB> *)(T + ((u * 32 + t) * 16 + idx) * MB);
+#pragma unroll
+                        for (int r = 0; r < MB; ++r) p[r] += e.v[r];
+                    }
+                    const float sj = h2f(mt[u][s][j]);
+#pragma unroll
+                    for (int r = 0; r < MB; ++r) acc[r] += sj * p[r];
+                }
+                const float z = h2f(mt[u][s][Q]);
+#pragma unroll
+                for (int r = 0; r < MB; ++r) acc[r] += z * XS[(u * SEG + s) * MB + r];
+            }
+        }
+    }
+
+    if (!col_ok) return;
+#pragma unroll
+    for (int r = 0; r < MB; ++r) {
+        const int m = m0 + r;
+        if (m >= M) break;
+        if (nslices == 1) store_out(Y, (size_t)m * ldy + n, acc[r], out_f32);
+        else ws[((size_t)blockIdx.y * M + m) * N + n] = acc[r];
+    }
+}
+
+__global__ void __launch_bounds__(256)
+hlq_gemm_reduce_kernel(const float *__restrict__ ws, void *__restrict__ Y, long ldy, int M, int N,
+                       int nslices, int out_f32)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)M * N;
+    if (i >= total) return;
+    float acc = 0.f;
+    for (int s = 0; s < nslices; ++s) acc += ws[(size_t)s * total + i];
+    const size_t m = i / N, n = i % N;
+    store_out(Y, m * ldy + n, acc, out_f32);
+}
+
+struct GemmPlan {
+    int MB, chunks_per_slice, nslices, rowblocks;
+};
+
+GemmPlan plan_gemm(const HlqDims &dm, int64_t M)
+{
+    GemmPlan p;
+    p.MB = M >= 3 ? 4 : 2;
+    p.rowblocks = (int)((M + p.MB - 1) / p.MB);
+    const long ntiles = (dm.N + 255) / 256;
+    const long wg_cols = ntiles * p.rowblocks;
+    long want = (1024 + wg_cols - 1) / wg_cols;          // slices wanted to fill the chip
+    const long max_slices = (dm.nchunks + 1) / 2;        // a slice is at least one step (2 chunks)
+    if (want > max_slices) want = max_slices;
+    if (want < 1) want = 1;
+    int cps = (int)((dm.nchunks + want - 1) / want);
+    cps = (cps + 1) & ~1;                                 // whole steps
+    p.chunks_per_slice = cps;
+    p.nslices = (dm.nchunks + cps - 1) / cps;
+    return p;
+}
+
+template <int Q, int G, int MB>
+void launch_one(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const uint16_t *meta,
+                const uint16_t *X, long ldx, int M, void *Y, long ldy, float *ws, int out_f32,
+                hipStream_t st)
+{
+    const dim3 grid((unsigned)((dm.N + 255) / 256), (unsigned)p.nslices, (unsigned)p.rowblocks);
+    hlq_gemm_lut_kernel<Q, G, MB><<<grid, 256, 0, st>>>(bits, meta, X, ldx, M, Y, ldy, ws, dm.N, dm.nchunks,
+                                                        p.chunks_per_slice, p.nslices, out_f32);
+}
+
+template <int Q, int G>
+void launch_qg(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const uint16_t *meta,
+               const uint16_t *X, long ldx, int M, void *Y, long ldy, float *ws, int out_f32,
+               hipStream_t st)
+{
+    if (p.MB == 2) launch_one<Q, G, 2>(dm, p, bits, meta, X, ldx, M, Y, ldy, ws, out_f32, st);
+    else launch_one<Q, G, 4>(dm, p, bits, meta, X, ldx, M, Y, ldy, ws, out_f32, st);
+}
+
+template <int Q>
+hlq_status launch_q(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const uint16_t *meta,
+                    const uint16_t *X, long ldx, int M, void *Y, long ldy, float *ws, int out_f32,
+                    hipStream_t st)
+{
+    switch (dm.G) {
+    case 32: launch_qg<Q, 32>(dm, p, bits, meta, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    case 64: launch_qg<Q, 64>(dm, p, bits, meta, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    case 128: launch_qg<Q, 128>(dm, p, bits, meta, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    case 256: launch_qg<Q, 256>(dm, p, bits, meta, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    }
+    return HLQ_ERR_UNSUPPORTED;
+}
+
+} // namespace
+
+size_t hlq_gemm_ws_bytes(const HlqDims &dm, int64_t M)
+{
+    const GemmPlan p = plan_gemm(dm, M);
+    return p.nslices > 1 ? (size_t)p.nslices * (size_t)M * (size_t)dm.N * sizeof(float) : 0;
+}
+
+hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
+                           int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
+                           hipStream_t st)
+{
+    if (M > (int64_t)65535 * 2) return HLQ_ERR_UNSUPPORTED;   // grid.z limit
+    const GemmPlan p = plan_gemm(dm, M);
+    const uint4 *bits = (const uint4 *)packed;
+    const uint16_t *meta = (const uint16_t *)((const char *)packed + dm.bits_bytes);
+    const int out_f32 = out == HLQ_OUT_F32;
+    hlq_status s;
+    switch (dm.q) {
+    case 1: s = launch_q<1>(dm, p, bits, meta, X, (long)ldx, (int)M, Y, (long)ldy, (float *)ws, out_f32, st); break;
+    case 2: s = launch_q<2>(dm, p, bits, meta, X, (long)ldx, (int)M, Y, (long)ldy, (float *)ws, out_f32, st); break;
+    case 3: s = launch_q<3>(dm, p, bits, meta, X, (long)ldx, (int)M, Y, (long)ldy, (float *)ws, out_f32, st); break;
+    case 4: s = launch_q<4>(dm, p, bits, meta, X, (long)ldx, (int)M, Y, (long)ldy, (float *)ws, out_f32, st); break;
+    default: return HLQ_ERR_UNSUPPORTED;
+    }
+    if (s != HLQ_OK) return s;
+    if (p.nslices > 1) {
+        const size_t total = (size_t)M * dm.N;
+        const unsigned nb = (unsigned)((total + 255) / 256);
+        hlq_gemm_reduce_kernel<<<nb, 256, 0, st>>>((const float *)ws, Y, (long)ldy, (int)M, dm.N, p.nslices, out_f32);
+    }
+    return hlq_hip_status(hipGetLastError());
+}

@@ -1,0 +1,70 @@
+"""The five benchmark configurations at full size, HIP path vs the C oracle (all outputs at
+M = 1; sampled columns, all rows, where the oracle could not finish in seconds)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_oracle
+from oracle import hlq_oracle as O
+from paper_2510_19482_amd import synth
+
+from gpu_util import TOL, gemm_gpu, gemv_gpu, pack_on_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def check(shape, q, G, M, cfg, outliers, ncols=None):
+    say("config", cfg, shape.name, shape.K, shape.N, "q", q, "G", G, "M", M)
+    codes, S, Z = synth.make_weight(shape.K, shape.N, q, G, cfg, shape.name)
+    X = synth.make_x(M, shape.K, cfg, shape.name, outliers=outliers)
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    cols = None if ncols is None else synth.sample_columns(shape.N, ncols, cfg, shape.name)
+    ref = c_oracle.gemm_f64(X, codes, S, Z, q, G, cols=cols)
+    Y = gemv_gpu(d, packed, X[0]) if M == 1 else gemm_gpu(d, packed, X)
+    if cols is not None:
+        Y = Y[:, cols]
+    err = O.row_rel_err(Y, ref)
+    say("   max row err", float(err.max()))
+    assert err.max() <= TOL
+    del packed
+    torch.cuda.empty_cache()
+
+
+def test_config1_single_layer_decode():
+    check(synth.Shape("cfg1", 4096, 4096), 2, 128, 1, "cfg1", False)
+
+
+@pytest.mark.parametrize("q", [2, 3])
+@pytest.mark.parametrize("shape", synth.LLAMA31_8B_LAYER, ids=lambda s: s.name)
+def test_config2_8b_layer_decode(shape, q):
+    check(shape, q, 128, 1, "cfg2", False)
+
+
+@pytest.mark.parametrize("M", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("shape", [synth.LLAMA31_8B_LAYER[1], synth.LLAMA31_8B_LAYER[0],
+                                   synth.LLAMA31_8B_LAYER[6]], ids=lambda s: s.name)
+def test_config3_small_batch(shape, M):
+    check(shape, 4, 128, M, "cfg3", True)
+
+
+@pytest.mark.parametrize("M", [512, 2048])
+@pytest.mark.parametrize("shape", [synth.LLAMA31_8B_LAYER[1], synth.LLAMA31_8B_LAYER[6]], ids=lambda s: s.name)
+def test_config4_prefill(shape, M):
+    check(shape, 2, 128, M, "cfg4", True, ncols=48)
+
+
+@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("shape", [synth.LLAMA31_70B_LAYER[0], synth.LLAMA31_70B_LAYER[1],
+                                   synth.LLAMA31_70B_LAYER[4], synth.LLAMA31_70B_LAYER[6]], ids=lambda s: s.name)
+def test_config5_70b_layer_decode(shape, G):
+    check(shape, 2, G, 1, "cfg5", False, ncols=512)
+
+
+def test_config5_lm_head():
+    check(synth.LLAMA31_70B_LM_HEAD, 2, 128, 1, "cfg5", False, ncols=512)
