@@ -20,7 +20,10 @@
  *   - Argument errors are found on the host before anything is launched and are reported
  *     through the return code; nothing aborts or throws across this boundary.
  *   - Supported descriptors: 1 <= q <= 4, G in {32, 64, 128, 256}, K % 128 == 0,
- *     K % G == 0, N % 8 == 0, K, N >= 1, layout == hlq_layout_version().
+ *     K % G == 0, N % 8 == 0, K, N >= 1, layout == hlq_layout_version()
+ *     (anything else: HLQ_ERR_BAD_DESC); K <= 2^21 and N <= 2^20 (beyond: HLQ_ERR_UNSUPPORTED).
+ *   - Alignment: packed blobs and workspaces 16 bytes, activations 8 bytes, outputs their
+ *     element size; ldx a multiple of 4 when M > 1 (violations: HLQ_ERR_BAD_STRIDE).
  */
 #ifndef HLQ_H
 #define HLQ_H
@@ -38,7 +41,7 @@ typedef enum {
     HLQ_ERR_BAD_DESC = 2,         /* q, G, K, N or layout outside the supported set          */
     HLQ_ERR_UNSUPPORTED = 3,      /* valid request this build has no kernel for              */
     HLQ_ERR_BUFFER_TOO_SMALL = 4, /* packed / workspace buffer smaller than required         */
-    HLQ_ERR_BAD_STRIDE = 5,       /* ldx < K, ldy < N, or M < 0                              */
+    HLQ_ERR_BAD_STRIDE = 5,       /* ldx < K, ldy < N, M < 0, or a misaligned pointer / ldx  */
     HLQ_ERR_HIP = 6               /* the HIP runtime refused a launch                        */
 } hlq_status;
 
@@ -63,15 +66,23 @@ HLQ_API uint32_t hlq_layout_version(void);
 
 /* Size of the packed weight blob.  Equals K*N*(q/8 + 2*(q+1)/G) bytes: q one-bit planes
  * plus q fp16 scales and one fp16 zero per (group, column) -- the bits-per-weight
- * accounting of Table 1 (q + 16(q+1)/G).  `bits` / `meta` (optional, host) receive the
- * two parts; the planes come first in the blob, the scales/zeros start at byte `bits`.
- * Host-only, no GPU needed. */
+ * accounting of Table 1 (q + 16(q+1)/G); the layout adds no padding.  `bits` / `meta`
+ * (optional, host) receive the byte counts of the two parts (they are interleaved in the
+ * blob).  Host-only, no GPU needed. */
 HLQ_API hlq_status hlq_packed_bytes(const hlq_desc *d, size_t *total, size_t *bits, size_t *meta);
 
 /* Bytes of caller-provided workspace hlq_lut_gemv / hlq_lut_gemm need for M rows (host-only).
- * The workspace holds split-K partial sums; its contents are scratch between calls.
- * Two calls that may run concurrently need separate workspaces. */
+ * The workspace holds split-K arrival counters and partial sums.  It must be passed once
+ * through hlq_workspace_init after allocation; every call leaves it initialised, so one
+ * workspace can serve any number of successive calls (also of different shapes, if large
+ * enough for each).  Two calls that may run concurrently need separate workspaces. */
 HLQ_API hlq_status hlq_workspace_bytes(const hlq_desc *d, int64_t M, size_t *bytes);
+
+/* Workspace size for hlq_lut_gemv_batch over `count` descriptors (host array). */
+HLQ_API hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, size_t *bytes);
+
+/* Zero the arrival counters of a freshly allocated workspace (asynchronous on `stream`). */
+HLQ_API hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream);
 
 /* Offline step of App. B ("decomposed into q single-bit matrices offline") and of
  * App. D, Weight-Rearrange: split codes into bit-planes and store them so the runtime
@@ -93,6 +104,16 @@ HLQ_API hlq_status hlq_unpack(const hlq_desc *d, const void *packed, uint8_t *co
  *   ws / ws_bytes: workspace of at least hlq_workspace_bytes(d, 1). */
 HLQ_API hlq_status hlq_lut_gemv(const hlq_desc *d, const void *packed, const uint16_t *x, void *y,
                         hlq_out_dtype out, void *ws, size_t ws_bytes, void *stream);
+
+/* `count` (1..8) independent GEMVs y_i = x_i @ W^_i in ONE launch (the decode GEMVs of a
+ * layer that do not depend on each other, e.g. q/k/v or gate/up).  All descriptors must share
+ * q and G.  descs, packed, x, y are HOST arrays of length count; packed[i], x[i], y[i] are
+ * device pointers with the meaning they have in hlq_lut_gemv.  Results are identical to
+ * `count` separate hlq_lut_gemv calls up to fp32 summation order.
+ *   ws / ws_bytes: workspace of at least hlq_batch_workspace_bytes(count, descs). */
+HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const void *const *packed,
+                                      const uint16_t *const *x, void *const *y, hlq_out_dtype out,
+                                      void *ws, size_t ws_bytes, void *stream);
 
 /* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded
  * weight words shared by all rows).  X row-major with leading dimension ldx >= K (in

@@ -50,6 +50,13 @@ def _load() -> ctypes.CDLL:
     lib.hlq_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
     lib.hlq_lut_gemv.restype = ctypes.c_int
     lib.hlq_lut_gemv.argtypes = [dp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
+    lib.hlq_batch_workspace_bytes.restype = ctypes.c_int
+    lib.hlq_batch_workspace_bytes.argtypes = [ctypes.c_int, dp, szp]
+    lib.hlq_workspace_init.restype = ctypes.c_int
+    lib.hlq_workspace_init.argtypes = [vp, sz, vp]
+    lib.hlq_lut_gemv_batch.restype = ctypes.c_int
+    lib.hlq_lut_gemv_batch.argtypes = [ctypes.c_int, dp, ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                       ctypes.POINTER(vp), ctypes.c_int, vp, sz, vp]
     lib.hlq_lut_gemm.restype = ctypes.c_int
     lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     return lib
@@ -121,9 +128,47 @@ def hlq_unpack(desc: HlqDesc, packed, stream=None):
     return codes, scales, zeros
 
 
-def alloc_workspace(desc: HlqDesc, M: int, device="cuda"):
+def batch_workspace_bytes(descs) -> int:
+    arr = (HlqDesc * len(descs))(*descs)
+    w = ctypes.c_size_t()
+    _check("hlq_batch_workspace_bytes", lib.hlq_batch_workspace_bytes(len(descs), arr, ctypes.byref(w)))
+    return w.value
+
+
+def _new_workspace(nbytes: int, device, stream=None):
     import torch
-    return torch.empty(max(workspace_bytes(desc, M), 256), dtype=torch.uint8, device=device)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=device)
+    _check("hlq_workspace_init", lib.hlq_workspace_init(_ptr(ws), ws.numel(), _stream_ptr(stream)))
+    return ws
+
+
+def alloc_workspace(desc: HlqDesc, M: int, device="cuda", stream=None):
+    """Allocate and initialise a workspace for GEMV/GEMM calls on `desc` with up to M rows."""
+    return _new_workspace(workspace_bytes(desc, M), device, stream)
+
+
+def alloc_batch_workspace(descs, device="cuda", stream=None):
+    return _new_workspace(batch_workspace_bytes(descs), device, stream)
+
+
+class GemvBatch:
+    """Pre-marshalled arguments of one hlq_lut_gemv_batch call (host arrays built once)."""
+
+    def __init__(self, descs, packed, xs, ys, out_f32=False, ws=None):
+        n = len(descs)
+        self.n = n
+        self.descs = (HlqDesc * n)(*descs)
+        self.packed = (ctypes.c_void_p * n)(*[_ptr(p) for p in packed])
+        self.xs = (ctypes.c_void_p * n)(*[_ptr(x) for x in xs])
+        self.ys = (ctypes.c_void_p * n)(*[_ptr(y) for y in ys])
+        self.out = HLQ_OUT_F32 if out_f32 else HLQ_OUT_F16
+        self.ws = ws if ws is not None else alloc_batch_workspace(list(descs), xs[0].device)
+        self._keep = (list(packed), list(xs), list(ys))
+
+    def launch(self, stream=None):
+        _check("hlq_lut_gemv_batch", lib.hlq_lut_gemv_batch(
+            self.n, self.descs, self.packed, self.xs, self.ys, self.out, _ptr(self.ws),
+            self.ws.numel(), _stream_ptr(stream)))
 
 
 def hlq_lut_gemv(desc: HlqDesc, packed, x, y=None, out_f32: bool = False, ws=None, stream=None):

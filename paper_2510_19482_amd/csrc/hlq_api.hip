@@ -5,11 +5,12 @@
 hlq_status hlq_check_desc(const hlq_desc *d, HlqDims *out)
 {
     if (!d) return HLQ_ERR_NULL;
-    if (d->layout != HLQ_LAYOUT_V1) return HLQ_ERR_BAD_DESC;
+    if (d->layout != HLQ_LAYOUT_V2) return HLQ_ERR_BAD_DESC;
     if (d->q < 1 || d->q > 4) return HLQ_ERR_BAD_DESC;
     if (d->G != 32 && d->G != 64 && d->G != 128 && d->G != 256) return HLQ_ERR_BAD_DESC;
     if (d->K < 1 || d->N < 1) return HLQ_ERR_BAD_DESC;
     if (d->K % HLQ_CHUNK_K != 0 || d->K % d->G != 0 || d->N % 8 != 0) return HLQ_ERR_BAD_DESC;
+    if (d->K > HLQ_MAX_K || d->N > HLQ_MAX_N) return HLQ_ERR_UNSUPPORTED;
     if (out) {
         out->K = d->K;
         out->N = d->N;
@@ -17,11 +18,26 @@ hlq_status hlq_check_desc(const hlq_desc *d, HlqDims *out)
         out->G = d->G;
         out->nchunks = d->K / HLQ_CHUNK_K;
         out->ngroups = d->K / d->G;
+        out->ntiles = (d->N + HLQ_TILE_N - 1) / HLQ_TILE_N;
+        out->col_bytes = (size_t)out->nchunks * d->q * 16u + (size_t)out->ngroups * (d->q + 1) * 2u;
         out->bits_bytes = (size_t)d->q * (size_t)out->nchunks * (size_t)d->N * 16u;
         out->meta_bytes = (size_t)(d->q + 1) * (size_t)out->ngroups * (size_t)d->N * 2u;
     }
     return HLQ_OK;
 }
+
+// counters + the larger of the GEMV and GEMM partial-sum areas, rounded to 256 bytes
+static size_t ws_need(const HlqDims &dm, int64_t M)
+{
+    size_t part = hlq_gemv_partial_bytes(dm);
+    if (M > 1) {
+        const size_t pm = hlq_gemm_partial_bytes(dm, M);
+        if (pm > part) part = pm;
+    }
+    return (HLQ_WS_COUNTER_BYTES + part + 255u) & ~(size_t)255u;
+}
+
+static bool misaligned(const void *p, unsigned a) { return ((uintptr_t)p & (a - 1u)) != 0; }
 
 extern "C" {
 
@@ -41,7 +57,7 @@ const char *hlq_status_string(hlq_status s)
     return "unknown status";
 }
 
-uint32_t hlq_layout_version(void) { return HLQ_LAYOUT_V1; }
+uint32_t hlq_layout_version(void) { return HLQ_LAYOUT_V2; }
 
 hlq_status hlq_packed_bytes(const hlq_desc *d, size_t *total, size_t *bits, size_t *meta)
 {
@@ -62,11 +78,31 @@ hlq_status hlq_workspace_bytes(const hlq_desc *d, int64_t M, size_t *bytes)
     if (s != HLQ_OK) return s;
     if (!bytes) return HLQ_ERR_NULL;
     if (M < 0) return HLQ_ERR_BAD_STRIDE;
-    size_t b = M <= 1 ? hlq_gemv_ws_bytes(dm) : hlq_gemm_ws_bytes(dm, M);
-    size_t b1 = hlq_gemv_ws_bytes(dm);
-    if (b1 > b) b = b1;
+    *bytes = ws_need(dm, M);
+    return HLQ_OK;
+}
+
+hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, size_t *bytes)
+{
+    if (!descs || !bytes) return HLQ_ERR_NULL;
+    if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
+    size_t b = HLQ_WS_COUNTER_BYTES;
+    for (int i = 0; i < count; ++i) {
+        HlqDims dm;
+        hlq_status s = hlq_check_desc(&descs[i], &dm);
+        if (s != HLQ_OK) return s;
+        b += hlq_gemv_partial_bytes(dm);
+    }
     *bytes = (b + 255u) & ~(size_t)255u;
     return HLQ_OK;
+}
+
+hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream)
+{
+    if (!ws) return HLQ_ERR_NULL;
+    if (ws_bytes < HLQ_WS_COUNTER_BYTES) return HLQ_ERR_BUFFER_TOO_SMALL;
+    if (((uintptr_t)ws & 15u) != 0) return HLQ_ERR_BAD_STRIDE;
+    return hlq_launch_ws_init(ws, ws_bytes, (hipStream_t)stream);
 }
 
 hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint16_t *scales,
@@ -96,12 +132,43 @@ hlq_status hlq_lut_gemv(const hlq_desc *d, const void *packed, const uint16_t *x
     HlqDims dm;
     hlq_status s = hlq_check_desc(d, &dm);
     if (s != HLQ_OK) return s;
-    if (!packed || !x || !y) return HLQ_ERR_NULL;
+    if (!packed || !x || !y || !ws) return HLQ_ERR_NULL;
     if (out != HLQ_OUT_F16 && out != HLQ_OUT_F32) return HLQ_ERR_UNSUPPORTED;
-    size_t need = hlq_gemv_ws_bytes(dm);
-    if (need > 0 && !ws) return HLQ_ERR_NULL;
+    if (misaligned(packed, 16) || misaligned(x, 8) || misaligned(ws, 16) || misaligned(y, out == HLQ_OUT_F32 ? 4 : 2))
+        return HLQ_ERR_BAD_STRIDE;
+    if (ws_bytes < HLQ_WS_COUNTER_BYTES + hlq_gemv_partial_bytes(dm)) return HLQ_ERR_BUFFER_TOO_SMALL;
+    HlqGemvItem it;
+    it.dm = dm;
+    it.packed = packed;
+    it.x = x;
+    it.y = y;
+    return hlq_launch_gemv_batch(1, &it, out, ws, (hipStream_t)stream);
+}
+
+hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const void *const *packed,
+                              const uint16_t *const *x, void *const *y, hlq_out_dtype out, void *ws,
+                              size_t ws_bytes, void *stream)
+{
+    if (!descs || !packed || !x || !y || !ws) return HLQ_ERR_NULL;
+    if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
+    if (out != HLQ_OUT_F16 && out != HLQ_OUT_F32) return HLQ_ERR_UNSUPPORTED;
+    if (misaligned(ws, 16)) return HLQ_ERR_BAD_STRIDE;
+    HlqGemvItem items[HLQ_MAX_BATCH];
+    size_t need = HLQ_WS_COUNTER_BYTES;
+    for (int i = 0; i < count; ++i) {
+        hlq_status s = hlq_check_desc(&descs[i], &items[i].dm);
+        if (s != HLQ_OK) return s;
+        if (descs[i].q != descs[0].q || descs[i].G != descs[0].G) return HLQ_ERR_UNSUPPORTED;
+        if (!packed[i] || !x[i] || !y[i]) return HLQ_ERR_NULL;
+        if (misaligned(packed[i], 16) || misaligned(x[i], 8) || misaligned(y[i], out == HLQ_OUT_F32 ? 4 : 2))
+            return HLQ_ERR_BAD_STRIDE;
+        items[i].packed = packed[i];
+        items[i].x = x[i];
+        items[i].y = y[i];
+        need += hlq_gemv_partial_bytes(items[i].dm);
+    }
     if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
-    return hlq_launch_gemv(dm, packed, x, y, out, ws, (hipStream_t)stream);
+    return hlq_launch_gemv_batch(count, items, out, ws, (hipStream_t)stream);
 }
 
 hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uint16_t *X, int64_t M,
@@ -114,16 +181,19 @@ hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uint16_t *X
     if (M < 0 || ldx < dm.K || ldy < dm.N) return HLQ_ERR_BAD_STRIDE;
     if (out != HLQ_OUT_F16 && out != HLQ_OUT_F32) return HLQ_ERR_UNSUPPORTED;
     if (M == 0) return HLQ_OK;
-    if (!packed || !X || !Y) return HLQ_ERR_NULL;
+    if (!packed || !X || !Y || !ws) return HLQ_ERR_NULL;
+    if (misaligned(packed, 16) || misaligned(X, 8) || misaligned(ws, 16) || misaligned(Y, out == HLQ_OUT_F32 ? 4 : 2))
+        return HLQ_ERR_BAD_STRIDE;
+    if (M > 1 && ldx % 4 != 0) return HLQ_ERR_BAD_STRIDE;   // rows are read as 8-byte words
+    if (ws_bytes < ws_need(dm, M)) return HLQ_ERR_BUFFER_TOO_SMALL;
     if (M == 1) {
-        size_t need1 = hlq_gemv_ws_bytes(dm);
-        if (need1 > 0 && !ws) return HLQ_ERR_NULL;
-        if (ws_bytes < need1) return HLQ_ERR_BUFFER_TOO_SMALL;
-        return hlq_launch_gemv(dm, packed, X, Y, out, ws, (hipStream_t)stream);
+        HlqGemvItem it;
+        it.dm = dm;
+        it.packed = packed;
+        it.x = X;
+        it.y = Y;
+        return hlq_launch_gemv_batch(1, &it, out, ws, (hipStream_t)stream);
     }
-    size_t need = hlq_gemm_ws_bytes(dm, M);
-    if (need > 0 && !ws) return HLQ_ERR_NULL;
-    if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
     return hlq_launch_gemm(dm, packed, X, M, ldx, Y, ldy, out, ws, (hipStream_t)stream);
 }
 

@@ -24,7 +24,7 @@ template <> struct RowVec<4> { float v[4]; };
 
 template <int Q, int G, int MB>
 __global__ void __launch_bounds__(256)
-hlq_gemm_lut_kernel(const uint4 *__restrict__ bits, const uint16_t *__restrict__ meta,
+hlq_gemm_lut_kernel(const char *__restrict__ packed, size_t col_bytes,
                     const uint16_t *__restrict__ X, long ldx, int M, void *__restrict__ Y, long ldy,
                     float *__restrict__ ws, int N, int nchunks, int chunks_per_slice, int nslices,
                     int out_f32)
@@ -41,6 +41,9 @@ hlq_gemm_lut_kernel(const uint4 *__restrict__ bits, const uint16_t *__restrict__
     const int tid = threadIdx.x;
     const int n = blockIdx.x * 256 + tid;
     const bool col_ok = n < N;
+    const int tile = n / HLQ_TILE_N, lane = n % HLQ_TILE_N;   // wavefront <-> column tile
+    const int tw = col_ok ? hlq_tile_width(tile, N) : 0;
+    const char *tile_base = packed + (size_t)tile * HLQ_TILE_N * col_bytes;
     const int m0 = blockIdx.z * MB;
     const int cbeg = blockIdx.y * chunks_per_slice;
     const int cend = min(cbeg + chunks_per_slice, nchunks);
@@ -56,16 +59,21 @@ hlq_gemm_lut_kernel(const uint4 *__restrict__ bits, const uint16_t *__restrict__
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u;
             const bool ok = col_ok && c < cend;
+            const char *rec = tile_base + (size_t)tw * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
 #pragma unroll
             for (int j = 0; j < Q; ++j)
-                w[u][j] = ok ? bits[((size_t)j * nchunks + c) * N + n] : make_uint4(0u, 0u, 0u, 0u);
+                w[u][j] = ok ? ((const uint4 *)rec)[j * tw + lane] : make_uint4(0u, 0u, 0u, 0u);
+            const char *mrec = rec;
+            if (G > 128) {   // the group's meta sits in the record of its first (even) chunk
+                const int ce = c & ~1;
+                mrec = tile_base + (size_t)tw * ((size_t)ce * Q * 16 + (size_t)hlq_groups_before(ce, G) * (Q + 1) * 2);
+            }
+            const uint16_t *mp = (const uint16_t *)(mrec + (size_t)tw * Q * 16);
 #pragma unroll
-            for (int s = 0; s < SEG; ++s) {
-                const int g = (G >= 128) ? (c * 128) / G : c * SEG + s;
+            for (int s = 0; s < SEG; ++s)
 #pragma unroll
                 for (int r = 0; r <= Q; ++r)
-                    mt[u][s][r] = ok ? meta[((size_t)g * (Q + 1) + r) * N + n] : (uint16_t)0;
-            }
+                    mt[u][s][r] = ok ? mp[(s * (Q + 1) + r) * tw + lane] : (uint16_t)0;
         }
 
         __syncthreads();   // readers of the previous step's tables are done
@@ -169,7 +177,7 @@ GemmPlan plan_gemm(const HlqDims &dm, int64_t M)
 }
 
 template <int Q, int G, int MB>
-void launch_one(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const uint16_t *meta,
+void launch_one(const HlqDims &dm, const GemmPlan &p, const char *bits, size_t meta,
                 const uint16_t *X, long ldx, int M, void *Y, long ldy, float *ws, int out_f32,
                 hipStream_t st)
 {
@@ -179,7 +187,7 @@ void launch_one(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const u
 }
 
 template <int Q, int G>
-void launch_qg(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const uint16_t *meta,
+void launch_qg(const HlqDims &dm, const GemmPlan &p, const char *bits, size_t meta,
                const uint16_t *X, long ldx, int M, void *Y, long ldy, float *ws, int out_f32,
                hipStream_t st)
 {
@@ -188,7 +196,7 @@ void launch_qg(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const ui
 }
 
 template <int Q>
-hlq_status launch_q(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, const uint16_t *meta,
+hlq_status launch_q(const HlqDims &dm, const GemmPlan &p, const char *bits, size_t meta,
                     const uint16_t *X, long ldx, int M, void *Y, long ldy, float *ws, int out_f32,
                     hipStream_t st)
 {
@@ -203,7 +211,7 @@ hlq_status launch_q(const HlqDims &dm, const GemmPlan &p, const uint4 *bits, con
 
 } // namespace
 
-size_t hlq_gemm_ws_bytes(const HlqDims &dm, int64_t M)
+size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
 {
     const GemmPlan p = plan_gemm(dm, M);
     return p.nslices > 1 ? (size_t)p.nslices * (size_t)M * (size_t)dm.N * sizeof(float) : 0;
@@ -215,9 +223,10 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
 {
     if (M > (int64_t)65535 * 2) return HLQ_ERR_UNSUPPORTED;   // grid.z limit
     const GemmPlan p = plan_gemm(dm, M);
-    const uint4 *bits = (const uint4 *)packed;
-    const uint16_t *meta = (const uint16_t *)((const char *)packed + dm.bits_bytes);
+    const char *bits = (const char *)packed;
+    const size_t meta = dm.col_bytes;
     const int out_f32 = out == HLQ_OUT_F32;
+    ws = (char *)ws + HLQ_WS_COUNTER_BYTES;   // partial sums follow the counter block
     hlq_status s;
     switch (dm.q) {
     case 1: s = launch_q<1>(dm, p, bits, meta, X, (long)ldx, (int)M, Y, (long)ldy, (float *)ws, out_f32, st); break;

@@ -8,53 +8,87 @@
 #include "hlq.h"
 
 // ---------------------------------------------------------------------------------------
-// Packed layout, version 1 (designed for 128-bit coalesced loads on CDNA4):
+// Packed layout "HLQ2" (designed for 128-bit coalesced loads by 64-wide wavefronts):
 //
-//   bits region, q*K*N/8 bytes, as 16-byte words  bits[j][c][n]:
-//       j < q       bit-plane
-//       c < K/128   "chunk" = 128 consecutive k (k = 128c .. 128c+127)
-//       n < N       output column
-//     The 16 bytes are four little-endian 32-bit words; bit b of word d is the plane-j bit
-//     of weight (k = 128c + 32d + b, n).  A 4-bit slice [4i+3:4i] of word d is therefore
-//     the table index for activations k = 128c + 32d + 4i .. +3 (bit r <-> k + r).
-//     Consecutive n are consecutive 16-byte words: a wavefront whose lanes own 64
-//     adjacent columns reads 1 KiB contiguous per load instruction.
+// The matrix is cut into column tiles of 64 columns (the last tile holds N - 64*tile
+// columns, a multiple of 8) and into chunks of 128 consecutive k.  Everything one
+// wavefront needs for (tile, chunk) is one contiguous record, and the records of a tile
+// follow each other in chunk order, so a wavefront that walks K for its 64 columns reads
+// one contiguous byte stream:
 //
-//   meta region, 2*(q+1)*(K/G)*N bytes, fp16  meta[g][r][n]:
-//       g < K/G, r < q: scale s_r[g, n];  r == q: zero z[g, n].
-//     Consecutive n are consecutive halfs.
+//   blob      = tile 0 | tile 1 | ...                 tile t starts at 64*t*col_bytes
+//   col_bytes = (K/128)*q*16 + (K/G)*(q+1)*2          bytes per column
+//   tile      = record(c=0) | record(c=1) | ...
+//   record(c) = bits[j<q][lane<w][16 bytes]           w = tile width
+//               meta[s][r<=q][lane<w] fp16             for the quant groups g that START in
+//                                                      chunk c (s = their index in the chunk):
+//                                                      r < q scale s_r[g, n], r == q zero z[g, n]
+//
+//   The 16 bytes of (plane j, lane) are four little-endian 32-bit words; bit b of word d is
+//   the plane-j bit of weight (k = 128c + 32d + b, n = 64*tile + lane).  A 4-bit slice
+//   [4i+3:4i] of word d is thus the table index for activations k = 128c + 32d + 4i .. +3
+//   (bit r <-> k + r).  With G = 256 a group spans two chunks; its meta sits in the even one.
+//
+// Total size is exactly K*N*q/8 + 2*(q+1)*(K/G)*N bytes: no padding anywhere.
 // ---------------------------------------------------------------------------------------
-#define HLQ_LAYOUT_V1 0x484c5131u /* "HLQ1" */
+#define HLQ_LAYOUT_V2 0x484c5132u /* "HLQ2" */
 #define HLQ_CHUNK_K 128
+#define HLQ_TILE_N 64
+#define HLQ_MAX_K (1 << 21)
+#define HLQ_MAX_N (1 << 20)
 
 struct HlqDims {
     int K, N, q, G;
     int nchunks;   // K / 128
     int ngroups;   // K / G
+    int ntiles;    // ceil(N / 64)
+    size_t col_bytes;
     size_t bits_bytes;
     size_t meta_bytes;
 };
 
-hlq_status hlq_check_desc(const hlq_desc *d, HlqDims *out);
+// groups whose meta is stored before chunk c of a tile
+__host__ __device__ __forceinline__ int hlq_groups_before(int c, int G) { return (c * HLQ_CHUNK_K + G - 1) / G; }
 
-// Split-K plan for the LUT kernels: every workgroup owns `chunks_per_wg` consecutive chunks
-// of K for a tile of columns; `nslices` partial results per output are then reduced.
-struct HlqPlan {
-    int chunks_per_wg;
-    int nslices;
-};
-HlqPlan hlq_plan_gemv(const HlqDims &dm);
+__host__ __device__ __forceinline__ int hlq_tile_width(int tile, int N)
+{
+    const int w = N - tile * HLQ_TILE_N;
+    return w < HLQ_TILE_N ? w : HLQ_TILE_N;
+}
+
+// byte offset of record (tile, c); w = tile width
+__host__ __device__ __forceinline__ size_t hlq_rec_off(size_t col_bytes, int tile, int w, int c, int q, int G)
+{
+    return (size_t)tile * HLQ_TILE_N * col_bytes +
+           (size_t)w * ((size_t)c * q * 16 + (size_t)hlq_groups_before(c, G) * (q + 1) * 2);
+}
+
+hlq_status hlq_check_desc(const hlq_desc *d, HlqDims *out);
 
 hlq_status hlq_launch_pack(const HlqDims &dm, const uint8_t *codes, const uint16_t *scales,
                            const uint16_t *zeros, void *packed, hipStream_t st);
 hlq_status hlq_launch_unpack(const HlqDims &dm, const void *packed, uint8_t *codes,
                              uint16_t *scales, uint16_t *zeros, hipStream_t st);
-hlq_status hlq_launch_gemv(const HlqDims &dm, const void *packed, const uint16_t *x, void *y,
-                           hlq_out_dtype out, void *ws, hipStream_t st);
+
+// One GEMV of a grouped launch (all problems of a launch share q and G).
+struct HlqGemvItem {
+    HlqDims dm;
+    const void *packed;
+    const uint16_t *x;
+    void *y;
+};
+#define HLQ_MAX_BATCH 8
+hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws,
+                                 hipStream_t st);
 hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
                            int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
                            hipStream_t st);
-size_t hlq_gemv_ws_bytes(const HlqDims &dm);
-size_t hlq_gemm_ws_bytes(const HlqDims &dm, int64_t M);
+hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st);
+
+// Workspace = [HLQ_WS_COUNTER_BYTES of split-K arrival counters][fp32 partial sums].
+// Counters are zero between calls (hlq_workspace_init zeroes them; kernels re-zero them).
+#define HLQ_WS_COUNTER_BYTES 131072
+size_t hlq_gemv_partial_bytes(const HlqDims &dm);
+size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M);
 
 static inline hlq_status hlq_hip_status(hipError_t e) { return e == hipSuccess ? HLQ_OK : HLQ_ERR_HIP; }

@@ -6,11 +6,11 @@
 namespace {
 
 // One thread per (chunk c, column n): gathers the 128 codes of that column slice and emits
-// one 16-byte word per bit-plane.  Threads of a wavefront own adjacent columns, so both the
-// byte reads (row k, columns n..n+63) and the 16-byte writes are contiguous.
+// one 16-byte word per bit-plane into record (tile, c).  Threads of a wavefront own adjacent
+// columns, so both the byte reads (row k, columns n..n+63) and the 16-byte writes are contiguous.
 __global__ void __launch_bounds__(256)
-hlq_pack_bits_kernel(const uint8_t *__restrict__ codes, uint4 *__restrict__ bits, int N,
-                     int nchunks, int q)
+hlq_pack_bits_kernel(const uint8_t *__restrict__ codes, char *__restrict__ packed, int N,
+                     size_t col_bytes, int q, int G)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
     const int c = blockIdx.y;
@@ -26,21 +26,24 @@ hlq_pack_bits_kernel(const uint8_t *__restrict__ codes, uint4 *__restrict__ bits
             for (int j = 0; j < 4; ++j) w[j][d] |= ((code >> j) & 1u) << b;
         }
     }
-    for (int j = 0; j < q; ++j)
-        bits[((size_t)j * nchunks + c) * N + n] = make_uint4(w[j][0], w[j][1], w[j][2], w[j][3]);
+    const int tile = n / HLQ_TILE_N, lane = n % HLQ_TILE_N, tw = hlq_tile_width(tile, N);
+    uint4 *rec = (uint4 *)(packed + hlq_rec_off(col_bytes, tile, tw, c, q, G));
+    for (int j = 0; j < q; ++j) rec[j * tw + lane] = make_uint4(w[j][0], w[j][1], w[j][2], w[j][3]);
 }
 
 __global__ void __launch_bounds__(256)
-hlq_unpack_bits_kernel(const uint4 *__restrict__ bits, uint8_t *__restrict__ codes, int N,
-                       int nchunks, int q)
+hlq_unpack_bits_kernel(const char *__restrict__ packed, uint8_t *__restrict__ codes, int N,
+                       size_t col_bytes, int q, int G)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
     const int c = blockIdx.y;
     if (n >= N) return;
     uint32_t w[4][4];
+    const int tile = n / HLQ_TILE_N, lane = n % HLQ_TILE_N, tw = hlq_tile_width(tile, N);
+    const uint4 *rec = (const uint4 *)(packed + hlq_rec_off(col_bytes, tile, tw, c, q, G));
     for (int j = 0; j < 4; ++j) {
         uint4 v = make_uint4(0u, 0u, 0u, 0u);
-        if (j < q) v = bits[((size_t)j * nchunks + c) * N + n];
+        if (j < q) v = rec[j * tw + lane];
         w[j][0] = v.x; w[j][1] = v.y; w[j][2] = v.z; w[j][3] = v.w;
     }
     uint8_t *dst = codes + (size_t)c * HLQ_CHUNK_K * N + n;
@@ -54,30 +57,42 @@ hlq_unpack_bits_kernel(const uint4 *__restrict__ bits, uint8_t *__restrict__ cod
     }
 }
 
-// meta[g][r][n] <- r < q ? scales[r][g][n] : zeros[g][n]   (and the inverse)
+// Address of the fp16 slot (group g, row r, column n) inside the record of the chunk in which
+// group g starts.
+__device__ __forceinline__ size_t meta_slot(size_t col_bytes, int N, int q, int G, int g, int r, int n)
+{
+    const int tile = n / HLQ_TILE_N, lane = n % HLQ_TILE_N, tw = hlq_tile_width(tile, N);
+    const int c = (int)(((long)g * G) / HLQ_CHUNK_K);
+    const int s = g - hlq_groups_before(c, G);
+    return hlq_rec_off(col_bytes, tile, tw, c, q, G) + (size_t)tw * q * 16 +
+           ((size_t)(s * (q + 1) + r) * tw + lane) * 2;
+}
+
+// record meta <- r < q ? scales[r][g][n] : zeros[g][n]   (and the inverse)
 __global__ void __launch_bounds__(256)
 hlq_pack_meta_kernel(const uint16_t *__restrict__ scales, const uint16_t *__restrict__ zeros,
-                     uint16_t *__restrict__ meta, int N, int ngroups, int q)
+                     char *__restrict__ packed, int N, size_t col_bytes, int ngroups, int q, int G)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
     const int g = blockIdx.y;
     if (n >= N) return;
     for (int r = 0; r < q; ++r)
-        meta[((size_t)g * (q + 1) + r) * N + n] = scales[((size_t)r * ngroups + g) * N + n];
-    meta[((size_t)g * (q + 1) + q) * N + n] = zeros[(size_t)g * N + n];
+        *(uint16_t *)(packed + meta_slot(col_bytes, N, q, G, g, r, n)) = scales[((size_t)r * ngroups + g) * N + n];
+    *(uint16_t *)(packed + meta_slot(col_bytes, N, q, G, g, q, n)) = zeros[(size_t)g * N + n];
 }
 
 __global__ void __launch_bounds__(256)
-hlq_unpack_meta_kernel(const uint16_t *__restrict__ meta, uint16_t *__restrict__ scales,
-                       uint16_t *__restrict__ zeros, int N, int ngroups, int q)
+hlq_unpack_meta_kernel(const char *__restrict__ packed, uint16_t *__restrict__ scales,
+                       uint16_t *__restrict__ zeros, int N, size_t col_bytes, int ngroups, int q, int G)
 {
     const int n = blockIdx.x * 256 + threadIdx.x;
     const int g = blockIdx.y;
     if (n >= N) return;
     if (scales)
         for (int r = 0; r < q; ++r)
-            scales[((size_t)r * ngroups + g) * N + n] = meta[((size_t)g * (q + 1) + r) * N + n];
-    if (zeros) zeros[(size_t)g * N + n] = meta[((size_t)g * (q + 1) + q) * N + n];
+            scales[((size_t)r * ngroups + g) * N + n] =
+                *(const uint16_t *)(packed + meta_slot(col_bytes, N, q, G, g, r, n));
+    if (zeros) zeros[(size_t)g * N + n] = *(const uint16_t *)(packed + meta_slot(col_bytes, N, q, G, g, q, n));
 }
 
 } // namespace
@@ -86,10 +101,9 @@ hlq_status hlq_launch_pack(const HlqDims &dm, const uint8_t *codes, const uint16
                            const uint16_t *zeros, void *packed, hipStream_t st)
 {
     const unsigned ntiles = (unsigned)((dm.N + 255) / 256);
-    uint4 *bits = (uint4 *)packed;
-    uint16_t *meta = (uint16_t *)((char *)packed + dm.bits_bytes);
-    hlq_pack_bits_kernel<<<dim3(ntiles, dm.nchunks), 256, 0, st>>>(codes, bits, dm.N, dm.nchunks, dm.q);
-    hlq_pack_meta_kernel<<<dim3(ntiles, dm.ngroups), 256, 0, st>>>(scales, zeros, meta, dm.N, dm.ngroups, dm.q);
+    hlq_pack_bits_kernel<<<dim3(ntiles, dm.nchunks), 256, 0, st>>>(codes, (char *)packed, dm.N, dm.col_bytes, dm.q, dm.G);
+    hlq_pack_meta_kernel<<<dim3(ntiles, dm.ngroups), 256, 0, st>>>(scales, zeros, (char *)packed, dm.N, dm.col_bytes,
+                                                                   dm.ngroups, dm.q, dm.G);
     return hlq_hip_status(hipGetLastError());
 }
 
@@ -97,11 +111,11 @@ hlq_status hlq_launch_unpack(const HlqDims &dm, const void *packed, uint8_t *cod
                              uint16_t *scales, uint16_t *zeros, hipStream_t st)
 {
     const unsigned ntiles = (unsigned)((dm.N + 255) / 256);
-    const uint4 *bits = (const uint4 *)packed;
-    const uint16_t *meta = (const uint16_t *)((const char *)packed + dm.bits_bytes);
     if (codes)
-        hlq_unpack_bits_kernel<<<dim3(ntiles, dm.nchunks), 256, 0, st>>>(bits, codes, dm.N, dm.nchunks, dm.q);
+        hlq_unpack_bits_kernel<<<dim3(ntiles, dm.nchunks), 256, 0, st>>>((const char *)packed, codes, dm.N, dm.col_bytes,
+                                                                         dm.q, dm.G);
     if (scales || zeros)
-        hlq_unpack_meta_kernel<<<dim3(ntiles, dm.ngroups), 256, 0, st>>>(meta, scales, zeros, dm.N, dm.ngroups, dm.q);
+        hlq_unpack_meta_kernel<<<dim3(ntiles, dm.ngroups), 256, 0, st>>>((const char *)packed, scales, zeros, dm.N,
+                                                                         dm.col_bytes, dm.ngroups, dm.q, dm.G);
     return hlq_hip_status(hipGetLastError());
 }
