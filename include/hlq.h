@@ -115,6 +115,13 @@ HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const vo
                                       const uint16_t *const *x, void *const *y, hlq_out_dtype out,
                                       void *ws, size_t ws_bytes, void *stream);
 
+/* Tuning knob (process-wide, not thread-safe; for benchmarks and tests): force the launch shape
+ * of the GEMV kernel -- column tiles per wavefront (1 or 2), wavefronts per workgroup (1..16),
+ * chunks of 128 k per wavefront -- instead of the built-in choice.  0 leaves a value automatic.
+ * Results stay within the documented tolerance for every setting; only speed changes.
+ * Values outside the ranges above: HLQ_ERR_UNSUPPORTED. */
+HLQ_API hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int chunks_per_wave);
+
 /* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded
  * weight words shared by all rows).  X row-major with leading dimension ldx >= K (in
  * elements), Y row-major with ldy >= N.  M = 0 is a no-op.

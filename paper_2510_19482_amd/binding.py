@@ -9,7 +9,7 @@ import ctypes
 import os
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_PKG, "libhlq.so")
+LIB_PATH = os.environ.get("HLQ_LIB", os.path.join(_PKG, "libhlq.so"))
 
 HLQ_OK = 0
 HLQ_OUT_F16 = 0
@@ -32,6 +32,11 @@ def _load() -> ctypes.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2510_19482_amd.build` "
             "(there is no CPU fallback)")
+    # torch ships its own copy of the HIP runtime (same SONAME as the system one).  It has to be
+    # loaded first: libhlq then binds to that copy, and both sides share one runtime, one device
+    # context and the same stream handles.  Loaded the other way round the process ends up with
+    # two runtimes and launches fail with "no ROCm-capable device".
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz, i64, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int64, ctypes.c_uint32
     dp = ctypes.POINTER(HlqDesc)
@@ -57,6 +62,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_lut_gemv_batch.restype = ctypes.c_int
     lib.hlq_lut_gemv_batch.argtypes = [ctypes.c_int, dp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                        ctypes.POINTER(vp), ctypes.c_int, vp, sz, vp]
+    lib.hlq_set_gemv_plan.restype = ctypes.c_int
+    lib.hlq_set_gemv_plan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.hlq_lut_gemm.restype = ctypes.c_int
     lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     return lib
@@ -80,6 +87,10 @@ def make_desc(K: int, N: int, q: int, G: int, layout: int | None = None) -> HlqD
 def _check(fn: str, status: int) -> None:
     if status != HLQ_OK:
         raise HlqError(fn, status)
+
+
+def set_gemv_plan(tiles_per_wave: int = 0, waves_per_workgroup: int = 0, chunks_per_wave: int = 0) -> None:
+    _check("hlq_set_gemv_plan", lib.hlq_set_gemv_plan(tiles_per_wave, waves_per_workgroup, chunks_per_wave))
 
 
 def packed_bytes(desc: HlqDesc):

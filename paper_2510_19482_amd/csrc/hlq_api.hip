@@ -105,6 +105,11 @@ hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream)
     return hlq_launch_ws_init(ws, ws_bytes, (hipStream_t)stream);
 }
 
+hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int chunks_per_wave)
+{
+    return hlq_gemv_plan_override(tiles_per_wave, waves_per_workgroup, chunks_per_wave);
+}
+
 hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint16_t *scales,
                     const uint16_t *zeros, void *packed, size_t packed_bytes, void *stream)
 {

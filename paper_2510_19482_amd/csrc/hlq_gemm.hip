@@ -221,6 +221,7 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
                            int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
                            hipStream_t st)
 {
+    hlq_clear_stale_error();
     if (M > (int64_t)65535 * 2) return HLQ_ERR_UNSUPPORTED;   // grid.z limit
     const GemmPlan p = plan_gemm(dm, M);
     const char *bits = (const char *)packed;

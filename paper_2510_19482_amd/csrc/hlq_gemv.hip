@@ -1,40 +1,43 @@
 // hlq_lut_gemv: M = 1 bit-serial LUT GEMV (Sec. 2 "Bit-Serial LUT-Based GEMM", App. B),
 // one launch for one or several independent GEMVs.
 //
-// Work split.  The unit of work is a wavefront: it owns one column tile (64 columns, lane <->
-// column) and a run of consecutive chunks (128 k each), i.e. one contiguous byte stream of the
-// packed blob.  Per chunk it
+// Work split.  The unit of work is a wavefront: it owns TN adjacent column tiles (64 columns
+// each, lane <-> column) and a run of consecutive chunks (128 k each), i.e. TN contiguous byte
+// streams of the packed blob.  Per chunk it
 //
-//   build    makes its OWN 32 tables in LDS (T[t][i] = sum_r bit_r(i) x[4t+r], App. B): lane
-//            (t, h) computes entries 8h .. 8h+7 of table t and stores them with two 128-bit LDS
-//            writes; the per-quant-group activation sums come from a shuffle reduction;
+//   build    makes its OWN 32 tables in LDS (T[t][i] = sum_r bit_r(i) x[4t+r], App. B; fp32
+//            entries): lane (t, h) computes entries 8h .. 8h+7 of table t and stores them with
+//            two 128-bit LDS writes; the per-quant-group activation sums come from a DPP
+//            reduction of exact fp32 dot products;
 //   consume  per plane and 4-bit slice one LDS lookup + one fp32 add; per (plane, quant group)
-//            one FMA with s_j; per quant group one FMA z * sum(x)   (Eq. 3 by linearity).
+//            one FMA with s_j; per quant group one FMA  z * sum(x)       (Eq. 3 by linearity).
 //
-// All lanes of the wavefront index the same 16-entry fp32 table at the same time: its entries
-// lie in 16 different LDS banks and equal addresses broadcast, so lookups are conflict-free by
+// All lanes of the wavefront index the same 16-entry table at the same time: its entries lie in
+// different LDS banks and equal addresses broadcast, so lookups are conflict-free by
 // construction.  Because tables are private to the wavefront and LDS operations of one
-// wavefront execute in order, the chunk loop has no barrier at all; the weight loads of chunk
-// c+1 are in flight while chunk c is consumed (two register sets).
+// wavefront execute in order, the chunk loop has no barrier at all; the weight loads of the next
+// NBUF-1 chunks are in flight while a chunk is consumed (NBUF register sets).
 //
-// The four wavefronts of a workgroup take four consecutive K ranges of the SAME tile and add
-// their results through LDS.  If K is also split across workgroups ("slices"), each workgroup
-// writes its partial sums to the workspace and bumps an arrival counter; the last one to arrive
-// adds the partials in slice order, so the result does not depend on arrival order.
+// The W wavefronts of a workgroup take W consecutive K ranges of the SAME tiles and add their
+// results through LDS.  If K is also split across workgroups ("slices"), each workgroup writes
+// its partial sums to the workspace and bumps an arrival counter; the last one to arrive adds
+// the partials in slice order, so the result does not depend on arrival order.
 #include <stdlib.h>
 
 #include "hlq_internal.h"
 
 namespace {
 
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+
 struct GemvProb {
     const char *packed;
     const uint16_t *x;
     void *y;
     float *part;       // [nslices][N] partial sums (nslices > 1)
-    int *cnt;          // [ntiles] arrival counters, zero between launches
+    int *cnt;          // [ntg] arrival counters, zero between launches
     size_t col_bytes;
-    int N, nchunks, ntiles, nslices, cps, blk_begin;
+    int N, nchunks, ntiles, ntg, nslices, cps, blk_begin;
 };
 
 struct GemvBatch {
@@ -51,12 +54,25 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
     else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
 }
 
-template <int Q, int G>
+// v + (v moved across lanes by DPP control CTRL), rows outside ROWMASK unchanged
+template <int CTRL, int ROWMASK = 0xf>
+__device__ __forceinline__ float add_dpp(float v)
+{
+    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, ROWMASK, 0xf, false);
+    return v + __builtin_bit_cast(float, moved);
+}
+
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+template <int Q, int G, int TN>
 struct ChunkRegs {
     static constexpr int GS = G < 128 ? G : 128;   // k covered by one scale inside a chunk
     static constexpr int SEG = 128 / GS;           // scale segments per chunk
-    uint32_t w[Q][4];
-    uint16_t mt[SEG][Q + 1];
+    uint32_t w[TN][Q][4];
+    uint16_t mt[TN][SEG][Q + 1];
     uint2 x;                                       // this lane's four activations (table build)
 };
 
@@ -70,6 +86,8 @@ struct ChunkRegs {
 // accumulates it: 2.25 VALU ops per lookup.  The LDS reads of word k+1 are issued before the
 // adds of word k.  The block drains the LDS queue on entry, so its own lgkmcnt arithmetic is
 // exact, and on exit, so every output is valid for the compiler.
+// (fp16 entries fetched pairwise into the halves of one register would save adds, but on this
+// part 16-bit LDS loads clear the other half of their destination, so the pairing is lost.)
 #define HLQ_LK1(R, AD, SRC, BYTE, T)                                                                          \
     "v_and_b32_sdwa " AD ", " SRC ", 60 dst_sel:BYTE_0 dst_unused:UNUSED_PRESERVE src0_sel:BYTE_" #BYTE        \
     " src1_sel:DWORD\n"                                                                                        \
@@ -150,158 +168,224 @@ __device__ __forceinline__ void lookup_words(const uint32_t (&w)[1], uint32_t (&
                  : "memory");
 }
 
-// All lookups of one chunk, then scales and zeros: compile-time recursion over (segment sg,
-// plane j) so that every LDS offset is an immediate.  xs[sg] = sum of the segment's activations.
-template <int Q, int G, int I = 0>
+// All lookups of one chunk, then scales and zeros: compile-time recursion over (tile tn,
+// segment sg, plane j) so that every LDS offset is an immediate.  xs[sg] = sum of the
+// segment's activations.
+template <int Q, int G, int TN, int I = 0>
 struct Consume {
-    using Regs = ChunkRegs<Q, G>;
+    using Regs = ChunkRegs<Q, G, TN>;
     static constexpr int SEG = Regs::SEG, WPS = Regs::GS / 32;
-    static constexpr int sg = I / Q, j = I % Q;
-    __device__ __forceinline__ static void run(const Regs &R, const float (&xs)[SEG], uint32_t (&ad)[4], float &acc)
+    static constexpr int tn = I / (SEG * Q), sg = (I / Q) % SEG, j = I % Q;
+    __device__ __forceinline__ static void run(const Regs &R, const float (&xs)[SEG], uint32_t (&ad)[4],
+                                               float (&acc)[TN])
     {
         uint32_t w[WPS];
 #pragma unroll
-        for (int d = 0; d < WPS; ++d) w[d] = R.w[j][sg * WPS + d];
+        for (int d = 0; d < WPS; ++d) w[d] = R.w[tn][j][sg * WPS + d];
         float p0 = 0.f, p1 = 0.f;
         lookup_words<sg * WPS * 8 * 64>(w, ad, p0, p1);
-        acc += h2f(R.mt[sg][j]) * (p0 + p1);
-        if (j == Q - 1) acc += h2f(R.mt[sg][Q]) * xs[sg];
-        Consume<Q, G, I + 1>::run(R, xs, ad, acc);
+        acc[tn] += h2f(R.mt[tn][sg][j]) * (p0 + p1);
+        if (j == Q - 1) acc[tn] += h2f(R.mt[tn][sg][Q]) * xs[sg];
+        Consume<Q, G, TN, I + 1>::run(R, xs, ad, acc);
     }
 };
-template <int Q, int G>
-struct Consume<Q, G, (128 / (G < 128 ? G : 128)) * Q> {
-    __device__ __forceinline__ static void run(const ChunkRegs<Q, G> &, const float (&)[128 / (G < 128 ? G : 128)],
-                                               uint32_t (&)[4], float &) {}
+template <int Q, int G, int TN>
+struct Consume<Q, G, TN, TN *(128 / (G < 128 ? G : 128)) * Q> {
+    __device__ __forceinline__ static void run(const ChunkRegs<Q, G, TN> &, const float (&)[128 / (G < 128 ? G : 128)],
+                                               uint32_t (&)[4], float (&)[TN]) {}
 };
 
-#define HLQ_GEMV_WAVES 4
+#ifndef HLQ_DEBUG_MODE
+#define HLQ_DEBUG_MODE 0   // 1: loads only (no lookups), 2: lookups only (no reloads) -- timing experiments
+#endif
 #define HLQ_GEMV_TABLE_BYTES 2048   // 32 tables x 16 entries x fp32, per wavefront
 
-// Register budget: two chunks of planes and scales are live at once; with many planes and many
-// small quant groups that needs more than the 128 VGPRs four wavefronts per SIMD leave each.
-template <int Q, int G>
-constexpr int gemv_min_waves() { return Q * (G < 128 ? 128 / G : 1) <= 6 ? 4 : 2; }
+// Register budget: two chunks of planes and scales are live at once.  A 1024-lane workgroup
+// leaves 128 VGPRs per lane; the heaviest shapes (many planes and many small quant groups)
+// need more and are limited to 512 lanes (8 wavefronts) per workgroup.
+constexpr int gemv_weight(int Q, int G, int TN) { return TN * Q * (G < 128 ? 128 / G : 1); }
+constexpr int gemv_max_threads(int Q, int G, int TN) { return gemv_weight(Q, G, TN) <= 12 ? 1024 : 512; }
+constexpr bool gemv_two_tiles_ok(int Q, int G) { return gemv_weight(Q, G, 2) <= 6; }
+// register sets (chunks in flight + 1): deeper where a set is small
+constexpr int gemv_nbuf(int Q, int G, int TN) { return gemv_weight(Q, G, TN) <= 2 ? 4 : gemv_weight(Q, G, TN) <= 4 ? 3 : 2; }
 
-template <int Q, int G>
-__global__ void __launch_bounds__(64 * HLQ_GEMV_WAVES) __attribute__((amdgpu_waves_per_eu(gemv_min_waves<Q, G>(), 8)))
+template <int Q, int G, int TN>
+__global__ void __launch_bounds__(gemv_max_threads(Q, G, TN))
 hlq_gemv_kernel(const GemvBatch b)
 {
-    using Regs = ChunkRegs<Q, G>;
+    using Regs = ChunkRegs<Q, G, TN>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
-    constexpr int TPS = GS / 4;          // tables per segment
-    // LDS (dynamic segment only): [waves][32 tables][16] fp32 | reduction scratch
+    constexpr int NBUF = gemv_nbuf(Q, G, TN);
+    const int W = (int)(blockDim.x >> 6);   // wavefronts per workgroup
+    // LDS (dynamic segment only): [W][32 tables][16] fp32 | reduction scratch [W-1][TN][64] fp32
     extern __shared__ __attribute__((aligned(256))) float lds[];
-    float *red = lds + HLQ_GEMV_WAVES * (HLQ_GEMV_TABLE_BYTES / 4);   // [waves-1][64]
+    float *red = lds + W * (HLQ_GEMV_TABLE_BYTES / 4);
 
-    // ---- which problem, which column tile, which K slice --------------------------------------
+    // ---- which problem, which column tile group, which K slice ---------------------------------
     int pi = 0;
     for (int i = 1; i < b.count; ++i)
         if ((int)blockIdx.x >= b.p[i].blk_begin) pi = i;
     const GemvProb &P = b.p[pi];
     const int local = (int)blockIdx.x - P.blk_begin;
-    const int tile = local / P.nslices, slice = local % P.nslices;
+    const int tg = local / P.nslices, slice = local % P.nslices;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int tw = hlq_tile_width(tile, P.N);
-    const bool col_ok = lane < tw;
-    const int lane_c = col_ok ? lane : tw - 1;   // clamped: loads stay in bounds, results of
-    const int n = tile * HLQ_TILE_N + lane;      // invalid lanes are dropped
-    // this wavefront's run of chunks: the slice is cut into HLQ_GEMV_WAVES near-equal parts
+    // this wavefront's run of chunks: the slice is cut into W near-equal parts
     const int sbeg = slice * P.cps;
     const int send = min(sbeg + P.cps, P.nchunks);
     const int len = send - sbeg;
-    const int cbeg = sbeg + (len * wave) / HLQ_GEMV_WAVES;
-    const int cend = sbeg + (len * (wave + 1)) / HLQ_GEMV_WAVES;
-    const char *tile_base = P.packed + (size_t)tile * HLQ_TILE_N * P.col_bytes;
+    const int cbeg = sbeg + (len * wave) / W;
+    const int cend = sbeg + (len * (wave + 1)) / W;
+
+    // per tile: width, validity, clamped lane (loads stay in bounds; results of invalid lanes and
+    // tiles are dropped), stream base
+    int tw[TN], lane_c[TN];
+    bool col_ok[TN];
+    const char *tile_base[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        const int tile = tg * TN + tn;
+        const int tile_c = tile < P.ntiles ? tile : P.ntiles - 1;
+        tw[tn] = hlq_tile_width(tile_c, P.N);
+        col_ok[tn] = tile < P.ntiles && lane < tw[tn];
+        lane_c[tn] = lane < tw[tn] ? lane : tw[tn] - 1;
+        tile_base[tn] = P.packed + (size_t)tile_c * HLQ_TILE_N * P.col_bytes;
+    }
 
     // table-build role of this lane: entries 8h .. 8h+7 of table t of the current chunk
     const int bt = lane >> 1, bh = lane & 1;
-    float *Tw = lds + wave * (HLQ_GEMV_TABLE_BYTES / 4);
+    char *Tw = (char *)lds + wave * HLQ_GEMV_TABLE_BYTES;
     // LDS byte address of this wavefront's tables, a multiple of 256
-    const uint32_t tbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) float *)Tw;
+    const uint32_t tbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)Tw;
     uint32_t ad[4] = {tbase, tbase, tbase, tbase};
 
     auto load_chunk = [&](int c, Regs &R) {
-        const char *rec = tile_base + (size_t)tw * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
 #pragma unroll
-        for (int j = 0; j < Q; ++j) {
-            const uint4 v = ((const uint4 *)rec)[j * tw + lane_c];
-            R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
+        for (int tn = 0; tn < TN; ++tn) {
+            const int w_ = tw[tn];
+            const char *rec = tile_base[tn] + (size_t)w_ * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                const uint4 v = ((const uint4 *)rec)[j * w_ + lane_c[tn]];
+                R.w[tn][j][0] = v.x; R.w[tn][j][1] = v.y; R.w[tn][j][2] = v.z; R.w[tn][j][3] = v.w;
+            }
+            const char *mrec = rec;
+            if (G > 128) {   // the group's meta sits in the record of its first (even) chunk
+                const int c0 = c & ~1;
+                mrec = tile_base[tn] + (size_t)w_ * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
+            }
+            const uint16_t *m = (const uint16_t *)(mrec + (size_t)w_ * Q * 16);
+#pragma unroll
+            for (int sg = 0; sg < SEG; ++sg)
+#pragma unroll
+                for (int r = 0; r <= Q; ++r) R.mt[tn][sg][r] = m[(sg * (Q + 1) + r) * w_ + lane_c[tn]];
         }
-        const char *mrec = rec;
-        if (G > 128) {   // the group's meta sits in the record of its first (even) chunk
-            const int c0 = c & ~1;
-            mrec = tile_base + (size_t)tw * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
-        }
-        const uint16_t *m = (const uint16_t *)(mrec + (size_t)tw * Q * 16);
-#pragma unroll
-        for (int sg = 0; sg < SEG; ++sg)
-#pragma unroll
-            for (int r = 0; r <= Q; ++r) R.mt[sg][r] = m[(sg * (Q + 1) + r) * tw + lane_c];
         R.x = *(const uint2 *)(P.x + (size_t)c * 128 + 4 * bt);
     };
 
-    float acc = 0.f;
+    float acc[TN];
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) acc[tn] = 0.f;
+
     auto step = [&](const Regs &R) {
-        // build: entries 8h .. 8h+7 of table bt;  entry i = sum_r bit_r(i) x_r
-        const float x0 = h2f((uint16_t)(R.x.x & 0xffffu)), x1 = h2f((uint16_t)(R.x.x >> 16));
-        const float x2 = h2f((uint16_t)(R.x.y & 0xffffu)), x3 = h2f((uint16_t)(R.x.y >> 16));
+        // build: entries 8h .. 8h+7 of table bt;  entry i = sum_r bit_r(i) x_r  (fp32)
+        const half2_t x01 = __builtin_bit_cast(half2_t, R.x.x), x23 = __builtin_bit_cast(half2_t, R.x.y);
+        const float x0 = (float)x01.x, x1 = (float)x01.y, x2 = (float)x23.x, x3 = (float)x23.y;
         const float e0 = bh ? x3 : 0.f;
         const float e1 = e0 + x0, e2 = e0 + x1, e3 = e1 + x1;
-        float4 *dst = (float4 *)(Tw + bt * 16 + bh * 8);
+        float4 *dst = (float4 *)(Tw + bt * 64 + bh * 32);
         dst[0] = make_float4(e0, e1, e2, e3);
         dst[1] = make_float4(e0 + x2, e1 + x2, e2 + x2, e3 + x2);
-        // sums of the segments' activations (both lanes of a table hold the table's total)
-        float tot = (x0 + x1) + (x2 + x3);
-#pragma unroll
-        for (int off = 2; off < 2 * TPS; off <<= 1) tot += __shfl_xor(tot, off);
+        // sums of the segments' activations: exact fp32 dot products with (1, 1), then a DPP
+        // reduction over the 16 lanes (8 tables, 32 k) of a row and, for larger groups, over rows
+        const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
+        float tot = __builtin_amdgcn_fdot2(x01, ones, 0.f, false);
+        tot = __builtin_amdgcn_fdot2(x23, ones, tot, false);
+        tot = add_dpp<0x4E>(tot);    // quad_perm [2,3,0,1]: the other table of the quad
+        tot = add_dpp<0x124>(tot);   // row_ror:4
+        tot = add_dpp<0x128>(tot);   // row_ror:8   -> every lane holds its row's 32-k sum
         float xs[SEG];
+        if (GS == 32) {
 #pragma unroll
-        for (int sg = 0; sg < SEG; ++sg)
-            xs[sg] = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, tot), sg * TPS * 2));
-        Consume<Q, G>::run(R, xs, ad, acc);
+            for (int sg = 0; sg < SEG; ++sg) xs[sg] = lane_value(tot, 16 * sg);
+        } else if (GS == 64) {
+            tot = add_dpp<0x142, 0xa>(tot);   // row_bcast15: rows 1, 3 += rows 0, 2
+            xs[0] = lane_value(tot, 31);
+            xs[SEG - 1] = lane_value(tot, 63);
+        } else {
+            tot = add_dpp<0x142, 0xa>(tot);
+            tot = add_dpp<0x143, 0xc>(tot);   // row_bcast31: rows 2, 3 += row 1
+            xs[0] = lane_value(tot, 63);
+        }
+        if (HLQ_DEBUG_MODE == 1) {
+#pragma unroll
+            for (int tn = 0; tn < TN; ++tn) {
+                uint32_t m = 0;
+#pragma unroll
+                for (int j = 0; j < Q; ++j) m ^= R.w[tn][j][0] ^ R.w[tn][j][1] ^ R.w[tn][j][2] ^ R.w[tn][j][3];
+                acc[tn] += (float)m * h2f(R.mt[tn][0][0]) + xs[0];
+            }
+        } else {
+            Consume<Q, G, TN>::run(R, xs, ad, acc);
+        }
     };
 
-    // ---- chunk loop: two register sets, loads of chunk c+1 in flight while c is consumed ----------
-    Regs RA, RB;
-    if (cbeg < cend) load_chunk(cbeg, RA);
-    if (cbeg + 1 < cend) load_chunk(cbeg + 1, RB);
-    for (int c = cbeg; c < cend; c += 2) {
-        step(RA);
-        if (c + 2 < cend) load_chunk(c + 2, RA);
-        if (c + 1 < cend) {
-            step(RB);
-            if (c + 3 < cend) load_chunk(c + 3, RB);
+    // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
+    // Every iteration issues the same number of loads (past the end of the run the last chunk is
+    // simply read again and ignored), so the wait before each step can leave exactly the younger
+    // sets' loads outstanding.
+    if (cbeg < cend) {
+        Regs R[NBUF];
+#pragma unroll
+        for (int i = 0; i < NBUF; ++i) load_chunk(min(cbeg + i, cend - 1), R[i]);
+        for (int c = cbeg; c < cend; c += NBUF) {
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i) {
+                if (c + i < cend) step(R[i]);
+                if (HLQ_DEBUG_MODE != 2) load_chunk(min(c + i + NBUF, cend - 1), R[i]);
+            }
         }
     }
 
-    // ---- add the four wavefronts' K ranges ------------------------------------------------------------
-    if (wave > 0) red[(wave - 1) * 64 + lane] = acc;
+    // ---- add the W wavefronts' K ranges ------------------------------------------------------------------
+    if (wave > 0) {
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn) red[((wave - 1) * TN + tn) * 64 + lane] = acc[tn];
+    }
     __syncthreads();
     if (wave > 0) return;
+    for (int w2 = 1; w2 < W; ++w2) {
 #pragma unroll
-    for (int w2 = 1; w2 < HLQ_GEMV_WAVES; ++w2) acc += red[(w2 - 1) * 64 + lane];
+        for (int tn = 0; tn < TN; ++tn) acc[tn] += red[((w2 - 1) * TN + tn) * 64 + lane];
+    }
 
     if (P.nslices == 1) {
-        if (col_ok) store_out(P.y, n, acc, b.out_f32);
+#pragma unroll
+        for (int tn = 0; tn < TN; ++tn)
+            if (col_ok[tn]) store_out(P.y, (size_t)(tg * TN + tn) * HLQ_TILE_N + lane, acc[tn], b.out_f32);
         return;
     }
     // ---- split-K across workgroups -----------------------------------------------------------------------
-    // Partial sums and the counter live at device scope: the store below writes through the
-    // XCD-local L2, the wavefront waits for its acknowledgement, and only then is the arrival
+    // Partial sums and the counter live at device scope: the stores below write through the
+    // XCD-local L2, the wavefront waits for their acknowledgement, and only then is the arrival
     // counted.  The last workgroup reads the partials with device-scope loads, which bypass its
     // own L2.  No cache-wide write-back or invalidate (as a device-scope fence would issue) is
     // needed, and none is used: it costs tens of microseconds per launch on this part.
-    if (col_ok)
-        __hip_atomic_store(&P.part[(size_t)slice * P.N + n], acc, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn)
+        if (col_ok[tn])
+            __hip_atomic_store(&P.part[(size_t)slice * P.N + (size_t)(tg * TN + tn) * HLQ_TILE_N + lane], acc[tn],
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int old = 0;
-    if (lane == 0) old = __hip_atomic_fetch_add(&P.cnt[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) old = __hip_atomic_fetch_add(&P.cnt[tg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     if (old != P.nslices - 1) return;
-    if (col_ok) {
+#pragma unroll
+    for (int tn = 0; tn < TN; ++tn) {
+        if (!col_ok[tn]) continue;
+        const size_t n = (size_t)(tg * TN + tn) * HLQ_TILE_N + lane;
         float a = 0.f;
         int sl = 0;
         for (; sl + 4 <= P.nslices; sl += 4) {   // four independent loads in flight, added in slice order
@@ -315,7 +399,7 @@ hlq_gemv_kernel(const GemvBatch b)
             a += __hip_atomic_load(&P.part[(size_t)sl * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         store_out(P.y, n, a, b.out_f32);
     }
-    if (lane == 0) __hip_atomic_store(&P.cnt[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (lane == 0) __hip_atomic_store(&P.cnt[tg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void __launch_bounds__(256) hlq_ws_init_kernel(int *p, int n)
@@ -324,17 +408,27 @@ __global__ void __launch_bounds__(256) hlq_ws_init_kernel(int *p, int n)
     if (i < n) p[i] = 0;
 }
 
-constexpr size_t gemv_lds_bytes() { return HLQ_GEMV_WAVES * HLQ_GEMV_TABLE_BYTES + (HLQ_GEMV_WAVES - 1) * 64 * 4; }
+size_t gemv_lds_bytes(int W, int TN) { return (size_t)W * HLQ_GEMV_TABLE_BYTES + (size_t)(W - 1) * TN * 64 * 4; }
+
+template <int Q, int G>
+void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int TN, hipStream_t st)
+{
+    const dim3 blk(64 * W);
+    if (TN == 2) {
+        if constexpr (gemv_two_tiles_ok(Q, G)) hlq_gemv_kernel<Q, G, 2><<<nblocks, blk, gemv_lds_bytes(W, 2), st>>>(b);
+    } else {
+        hlq_gemv_kernel<Q, G, 1><<<nblocks, blk, gemv_lds_bytes(W, 1), st>>>(b);
+    }
+}
 
 template <int Q>
-hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, hipStream_t st)
+hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, int TN, hipStream_t st)
 {
-    const dim3 blk(64 * HLQ_GEMV_WAVES);
     switch (G) {
-    case 32: hlq_gemv_kernel<Q, 32><<<nblocks, blk, gemv_lds_bytes(), st>>>(b); return HLQ_OK;
-    case 64: hlq_gemv_kernel<Q, 64><<<nblocks, blk, gemv_lds_bytes(), st>>>(b); return HLQ_OK;
-    case 128: hlq_gemv_kernel<Q, 128><<<nblocks, blk, gemv_lds_bytes(), st>>>(b); return HLQ_OK;
-    case 256: hlq_gemv_kernel<Q, 256><<<nblocks, blk, gemv_lds_bytes(), st>>>(b); return HLQ_OK;
+    case 32: launch_qg<Q, 32>(b, nblocks, W, TN, st); return HLQ_OK;
+    case 64: launch_qg<Q, 64>(b, nblocks, W, TN, st); return HLQ_OK;
+    case 128: launch_qg<Q, 128>(b, nblocks, W, TN, st); return HLQ_OK;
+    case 256: launch_qg<Q, 256>(b, nblocks, W, TN, st); return HLQ_OK;
     }
     return HLQ_ERR_UNSUPPORTED;
 }
@@ -345,32 +439,62 @@ int env_int(const char *name, int dflt)
     return v && *v ? atoi(v) : dflt;
 }
 
-// Chunks per workgroup (= per K slice) for a launch whose problems hold `units` (tile, chunk)
-// pairs in total: aim at a few workgroups per CU; a workgroup takes at least one chunk per
-// wavefront, and slice boundaries stay even (with G = 256 a group spans two chunks).
-int plan_cps(long units)
+// Launch shape for a batch holding `units` (tile, chunk) pairs in total.
+struct GemvPlan {
+    int TN;    // column tiles per wavefront (1 or 2)
+    int W;     // wavefronts per workgroup (K ranges added through LDS)
+    int cpw;   // target chunks per wavefront; a slice is W * cpw chunks (rounded to even)
+};
+
+// process-wide overrides set by hlq_set_gemv_plan (0 = automatic)
+int g_plan_tn = 0, g_plan_w = 0, g_plan_cpw = 0;
+
+GemvPlan plan_gemv(long units)
 {
-    static const int target_wgs = env_int("HLQ_TARGET_WGS", 1536);
-    long cps = units / target_wgs;
-    if (cps < HLQ_GEMV_WAVES) cps = HLQ_GEMV_WAVES;
-    return (int)((cps + 1) & ~1L);
+    static const int env_tn = env_int("HLQ_GEMV_TN", 0);
+    static const int env_w = env_int("HLQ_GEMV_W", 0);
+    static const int env_cpw = env_int("HLQ_GEMV_CPW", 0);
+    GemvPlan pl;
+    // Measured on MI355X (sweeps over TN x W x cpw on the 8B / 70B shapes): one tile per
+    // wavefront, four wavefronts per workgroup; short runs for launches that would otherwise
+    // not fill the wavefront slots, longer runs (fewer split-K partials) for large ones.
+    pl.TN = 1;
+    pl.W = 4;
+    pl.cpw = units >= 65536 ? 8 : 4;
+    if (env_tn) pl.TN = env_tn;
+    if (env_w) pl.W = env_w;
+    if (env_cpw) pl.cpw = env_cpw;
+    if (g_plan_tn) pl.TN = g_plan_tn;
+    if (g_plan_w) pl.W = g_plan_w;
+    if (g_plan_cpw) pl.cpw = g_plan_cpw;
+    return pl;
 }
 
+// chunks per K slice: a multiple of two (with G = 256 a group spans two chunks)
+int slice_chunks(const GemvPlan &pl) { return (pl.W * pl.cpw + 1) & ~1; }
 int slices_for(const HlqDims &dm, int cps) { return (dm.nchunks + cps - 1) / cps; }
 
 } // namespace
 
+hlq_status hlq_gemv_plan_override(int tn, int w, int cpw)
+{
+    if (tn < 0 || tn > 2 || w < 0 || w > 16 || cpw < 0) return HLQ_ERR_UNSUPPORTED;
+    g_plan_tn = tn;
+    g_plan_w = w;
+    g_plan_cpw = cpw;
+    return HLQ_OK;
+}
+
 size_t hlq_gemv_partial_bytes(const HlqDims &dm)
 {
-    // A launch with more problems only raises chunks-per-slice, so the slice count of the
-    // single-problem plan bounds what any batch containing this problem uses.
-    const long units = (long)dm.ntiles * dm.nchunks;
-    const int ns = slices_for(dm, plan_cps(units));
+    // Upper bound over every plan: slices are never shorter than 4 chunks.
+    const int ns = (dm.nchunks + 3) / 4;
     return ns > 1 ? (size_t)ns * (size_t)dm.N * sizeof(float) : 0;
 }
 
 hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st)
 {
+    hlq_clear_stale_error();
     if (bytes < HLQ_WS_COUNTER_BYTES) return HLQ_ERR_BUFFER_TOO_SMALL;
     const int n = HLQ_WS_COUNTER_BYTES / 4;
     hlq_ws_init_kernel<<<(n + 255) / 256, 256, 0, st>>>((int *)ws, n);
@@ -380,10 +504,20 @@ hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st)
 hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws,
                                  hipStream_t st)
 {
+    hlq_clear_stale_error();
     if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
     long units = 0;
     for (int i = 0; i < count; ++i) units += (long)items[i].dm.ntiles * items[i].dm.nchunks;
-    const int cps = plan_cps(units);
+    GemvPlan pl = plan_gemv(units);
+    {
+        const int q0 = items[0].dm.q, G0 = items[0].dm.G;
+        if (!gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
+        const int maxw = gemv_max_threads(q0, G0, pl.TN) / 64;
+        if (pl.W > maxw) pl.W = maxw;
+    }
+    if (pl.W < 1 || pl.W > 16 || (pl.TN != 1 && pl.TN != 2) || pl.cpw < 1) return HLQ_ERR_UNSUPPORTED;
+    int cps = slice_chunks(pl);
+    if (cps < 4) cps = 4;
 
     GemvBatch b;
     b.count = count;
@@ -402,14 +536,15 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         p.N = dm.N;
         p.nchunks = dm.nchunks;
         p.ntiles = dm.ntiles;
+        p.ntg = (dm.ntiles + pl.TN - 1) / pl.TN;
         p.nslices = slices_for(dm, cps);
         p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
         p.blk_begin = (int)blk;
         p.cnt = cnt + cnt_used;
         p.part = part;
-        blk += (long)p.ntiles * p.nslices;
+        blk += (long)p.ntg * p.nslices;
         if (p.nslices > 1) {
-            cnt_used += p.ntiles;
+            cnt_used += p.ntg;
             part += (size_t)p.nslices * dm.N;
         }
     }
@@ -419,10 +554,10 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     const int q = items[0].dm.q, G = items[0].dm.G;
     hlq_status s;
     switch (q) {
-    case 1: s = launch_q<1>(G, b, (unsigned)blk, st); break;
-    case 2: s = launch_q<2>(G, b, (unsigned)blk, st); break;
-    case 3: s = launch_q<3>(G, b, (unsigned)blk, st); break;
-    case 4: s = launch_q<4>(G, b, (unsigned)blk, st); break;
+    case 1: s = launch_q<1>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
+    case 2: s = launch_q<2>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
+    case 3: s = launch_q<3>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
+    case 4: s = launch_q<4>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
     default: return HLQ_ERR_UNSUPPORTED;
     }
     if (s != HLQ_OK) return s;

@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
 
 #include "hlq.h"
 
@@ -84,6 +86,7 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
                            int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
                            hipStream_t st);
 hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st);
+hlq_status hlq_gemv_plan_override(int tn, int w, int cpw);
 
 // Workspace = [HLQ_WS_COUNTER_BYTES of split-K arrival counters][fp32 partial sums].
 // Counters are zero between calls (hlq_workspace_init zeroes them; kernels re-zero them).
@@ -91,4 +94,14 @@ hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st);
 size_t hlq_gemv_partial_bytes(const HlqDims &dm);
 size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M);
 
-static inline hlq_status hlq_hip_status(hipError_t e) { return e == hipSuccess ? HLQ_OK : HLQ_ERR_HIP; }
+// HLQ_VERBOSE=1 in the environment prints the runtime's message for a failed launch to stderr.
+static inline hlq_status hlq_hip_status(hipError_t e)
+{
+    if (e == hipSuccess) return HLQ_OK;
+    const char *v = getenv("HLQ_VERBOSE");
+    if (v && *v && *v != '0') fprintf(stderr, "libhlq: HIP error %d: %s\n", (int)e, hipGetErrorString(e));
+    return HLQ_ERR_HIP;
+}
+// The runtime's "last error" is sticky per thread: drop whatever an earlier caller left there, so
+// that the check after our own launches reports our launches only.
+static inline void hlq_clear_stale_error() { (void)hipGetLastError(); }

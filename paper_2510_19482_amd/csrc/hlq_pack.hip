@@ -100,6 +100,7 @@ hlq_unpack_meta_kernel(const char *__restrict__ packed, uint16_t *__restrict__ s
 hlq_status hlq_launch_pack(const HlqDims &dm, const uint8_t *codes, const uint16_t *scales,
                            const uint16_t *zeros, void *packed, hipStream_t st)
 {
+    hlq_clear_stale_error();
     const unsigned ntiles = (unsigned)((dm.N + 255) / 256);
     hlq_pack_bits_kernel<<<dim3(ntiles, dm.nchunks), 256, 0, st>>>(codes, (char *)packed, dm.N, dm.col_bytes, dm.q, dm.G);
     hlq_pack_meta_kernel<<<dim3(ntiles, dm.ngroups), 256, 0, st>>>(scales, zeros, (char *)packed, dm.N, dm.col_bytes,
@@ -110,6 +111,7 @@ hlq_status hlq_launch_pack(const HlqDims &dm, const uint8_t *codes, const uint16
 hlq_status hlq_launch_unpack(const HlqDims &dm, const void *packed, uint8_t *codes,
                              uint16_t *scales, uint16_t *zeros, hipStream_t st)
 {
+    hlq_clear_stale_error();
     const unsigned ntiles = (unsigned)((dm.N + 255) / 256);
     if (codes)
         hlq_unpack_bits_kernel<<<dim3(ntiles, dm.nchunks), 256, 0, st>>>((const char *)packed, codes, dm.N, dm.col_bytes,

@@ -1,0 +1,96 @@
+"""Grouped launches and every launch shape of the GEMV kernel against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_oracle
+from oracle import hlq_oracle as O
+from paper_2510_19482_amd import binding as B
+from paper_2510_19482_amd import synth
+
+from gpu_util import TOL, dev, gemv_gpu, pack_on_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def auto_plan():
+    yield
+    B.set_gemv_plan(0, 0, 0)
+
+
+@pytest.mark.parametrize("tn,w,cpw", [(1, 1, 1), (1, 2, 3), (1, 4, 1), (1, 8, 2), (1, 16, 1), (2, 4, 2),
+                                      (2, 8, 1), (2, 16, 3), (2, 1, 64), (1, 4, 64)])
+@pytest.mark.parametrize("q,G", [(2, 128), (3, 128), (1, 64), (2, 256), (4, 32)])
+def test_gemv_every_launch_shape(tn, w, cpw, q, G):
+    K, N = 2304, 1096            # 18 chunks, 17 full tiles + a 8-column tail
+    say("plan", tn, w, cpw, "q", q, "G", G)
+    B.set_gemv_plan(tn, w, cpw)
+    codes, S, Z = synth.make_weight(K, N, q, G, "plans")
+    x = synth.make_x(1, K, "plans", outliers=True)
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    ref = O.gemm_dequant(x, codes, S, Z, q, G)
+    y = gemv_gpu(d, packed, x[0], out_f32=True)
+    assert O.row_rel_err(y, ref).max() <= 2e-5
+    y2 = gemv_gpu(d, packed, x[0], out_f32=True)
+    assert np.array_equal(y, y2)          # split-K order is fixed
+
+
+def test_bad_plan_rejected():
+    for args in [(3, 0, 0), (0, 17, 0), (-1, 0, 0), (0, 0, -2)]:
+        with pytest.raises(B.HlqError):
+            B.set_gemv_plan(*args)
+
+
+@pytest.mark.parametrize("q", [2, 3])
+def test_batch_equals_single_calls_and_oracle(q):
+    G = 128
+    shapes = [synth.Shape("a", 1024, 520), synth.Shape("b", 512, 64), synth.Shape("c", 2048, 1032),
+              synth.Shape("d", 1024, 8)]
+    descs, packs, xs, ys, refs = [], [], [], [], []
+    for s in shapes:
+        codes, S, Z = synth.make_weight(s.K, s.N, q, G, "batch", s.name)
+        x = synth.make_x(1, s.K, "batch", s.name)
+        d, p = pack_on_gpu(codes, S, Z, q, G)
+        descs.append(d); packs.append(p); xs.append(dev(x[0]))
+        ys.append(torch.full((s.N,), 7.0, dtype=torch.float32, device="cuda"))
+        refs.append(O.gemm_dequant(x, codes, S, Z, q, G))
+    batch = B.GemvBatch(descs, packs, xs, ys, out_f32=True)
+    for rep in range(2):                     # the workspace is reusable as is
+        batch.launch()
+        torch.cuda.synchronize()
+        for s, y, ref in zip(shapes, ys, refs):
+            got = y.cpu().numpy().astype(np.float64)[None, :]
+            assert O.row_rel_err(got, ref).max() <= 2e-5, s.name
+
+
+def test_batch_argument_errors():
+    import ctypes
+    d = B.make_desc(256, 64, 2, 128)
+    d3 = B.make_desc(256, 64, 3, 128)
+    arr = (B.HlqDesc * 2)(d, d3)
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    assert B.lib.hlq_lut_gemv_batch(2, arr, ptrs, ptrs, ptrs, 0, 0x1000, 1 << 30, None) == 3   # mixed q
+    assert B.lib.hlq_lut_gemv_batch(0, arr, ptrs, ptrs, ptrs, 0, 0x1000, 1 << 30, None) == 3
+    assert B.lib.hlq_lut_gemv_batch(9, arr, ptrs, ptrs, ptrs, 0, 0x1000, 1 << 30, None) == 3
+    arr2 = (B.HlqDesc * 2)(d, d)
+    assert B.lib.hlq_lut_gemv_batch(2, arr2, ptrs, ptrs, ptrs, 0, 0x1000, 16, None) == 4
+    assert B.lib.hlq_lut_gemv_batch(2, arr2, None, ptrs, ptrs, 0, 0x1000, 1 << 30, None) == 1
+
+
+def test_one_workspace_serves_different_shapes():
+    q, G = 2, 128
+    big = B.make_desc(4096, 4096, q, G)
+    ws = B.alloc_workspace(big, 1)
+    for (K, N) in [(4096, 4096), (512, 72), (2048, 1032), (4096, 4096)]:
+        codes, S, Z = synth.make_weight(K, N, q, G, "ws", K, N)
+        x = synth.make_x(1, K, "ws", K, N)
+        d, packed = pack_on_gpu(codes, S, Z, q, G)
+        y = B.hlq_lut_gemv(d, packed, dev(x[0]), out_f32=True, ws=ws)
+        torch.cuda.synchronize()
+        ref = c_oracle.gemm_f64(x, codes, S, Z, q, G)
+        assert O.row_rel_err(y.cpu().numpy().astype(np.float64)[None, :], ref).max() <= 2e-5
