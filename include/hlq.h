@@ -122,8 +122,16 @@ HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const vo
  * Values outside the ranges above: HLQ_ERR_UNSUPPORTED. */
 HLQ_API hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int chunks_per_wave);
 
+/* Tuning knob (process-wide, not thread-safe): formulation used by hlq_lut_gemm for M > 1.
+ * 0 = automatic (table lookups for small M, matrix cores from the measured crossover on),
+ * 1 = table lookups always, 2 = matrix cores always.  Other values: HLQ_ERR_UNSUPPORTED.
+ * The matrix-core formulation rebuilds W^ in fp16 registers and requires |s_j| < 512. */
+HLQ_API hlq_status hlq_set_gemm_path(int path);
+
 /* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded
- * weight words shared by all rows).  X row-major with leading dimension ldx >= K (in
+ * weight words shared by all rows; from the measured crossover in M on, the same product is
+ * computed as a dense contraction on the matrix cores with W^ rebuilt tile by tile in
+ * registers -- see hlq_set_gemm_path).  X row-major with leading dimension ldx >= K (in
  * elements), Y row-major with ldy >= N.  M = 0 is a no-op.
  *   ws / ws_bytes: workspace of at least hlq_workspace_bytes(d, M). */
 HLQ_API hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uint16_t *X, int64_t M,

@@ -64,6 +64,8 @@ def _load() -> ctypes.CDLL:
                                        ctypes.POINTER(vp), ctypes.c_int, vp, sz, vp]
     lib.hlq_set_gemv_plan.restype = ctypes.c_int
     lib.hlq_set_gemv_plan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.hlq_set_gemm_path.restype = ctypes.c_int
+    lib.hlq_set_gemm_path.argtypes = [ctypes.c_int]
     lib.hlq_lut_gemm.restype = ctypes.c_int
     lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     return lib
@@ -91,6 +93,13 @@ def _check(fn: str, status: int) -> None:
 
 def set_gemv_plan(tiles_per_wave: int = 0, waves_per_workgroup: int = 0, chunks_per_wave: int = 0) -> None:
     _check("hlq_set_gemv_plan", lib.hlq_set_gemv_plan(tiles_per_wave, waves_per_workgroup, chunks_per_wave))
+
+
+GEMM_AUTO, GEMM_LUT, GEMM_MFMA = 0, 1, 2
+
+
+def set_gemm_path(path: int = 0) -> None:
+    _check("hlq_set_gemm_path", lib.hlq_set_gemm_path(path))
 
 
 def packed_bytes(desc: HlqDesc):

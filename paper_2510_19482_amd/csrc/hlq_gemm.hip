@@ -211,13 +211,13 @@ hlq_status launch_q(const HlqDims &dm, const GemmPlan &p, const char *bits, size
 
 } // namespace
 
-size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
+size_t hlq_gemm_lut_partial_bytes(const HlqDims &dm, int64_t M)
 {
     const GemmPlan p = plan_gemm(dm, M);
     return p.nslices > 1 ? (size_t)p.nslices * (size_t)M * (size_t)dm.N * sizeof(float) : 0;
 }
 
-hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
+hlq_status hlq_launch_gemm_lut(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
                            int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
                            hipStream_t st)
 {
@@ -243,4 +243,37 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
         hlq_gemm_reduce_kernel<<<nb, 256, 0, st>>>((const float *)ws, Y, (long)ldy, (int)M, dm.N, p.nslices, out_f32);
     }
     return hlq_hip_status(hipGetLastError());
+}
+
+// ---- formulation choice ---------------------------------------------------------------------------
+// 0 = automatic (by M), 1 = table lookups (this file), 2 = matrix cores (hlq_gemm_mfma.hip)
+static int g_gemm_path = 0;
+
+hlq_status hlq_gemm_path_override(int path)
+{
+    if (path < 0 || path > 2) return HLQ_ERR_UNSUPPORTED;
+    g_gemm_path = path;
+    return HLQ_OK;
+}
+
+static bool use_mfma(int64_t M)
+{
+    if (g_gemm_path == 1) return false;
+    if (g_gemm_path == 2) return true;
+    // measured on MI355X (8B shapes, q = 2..4): the lookup kernel wins up to M = 4, from M = 8 on the
+    // matrix-core kernel is faster and the gap grows with M
+    return M >= 8;
+}
+
+size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
+{
+    const size_t a = hlq_gemm_lut_partial_bytes(dm, M), b = hlq_gemm_mfma_partial_bytes(dm, M);
+    return a > b ? a : b;
+}
+
+hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
+                           void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
+{
+    if (use_mfma(M)) return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
+    return hlq_launch_gemm_lut(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
 }

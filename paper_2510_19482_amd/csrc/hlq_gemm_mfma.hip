@@ -1,0 +1,356 @@
+// hlq_lut_gemm, dense-contraction formulation for larger M (the alternative the batched rows of
+// App. B allow once table construction no longer amortises: one table set per row costs
+// M*q*K*N/4 lookup-adds, a matrix-core contraction costs M*K*N MACs at ~60x the rate).
+//
+//   Y[M,N] = X[M,K] @ W^,   W^ = sum_j s_j b_j + z   (Eq. 3 / Eq. 6)
+//
+// W^ is rebuilt tile by tile IN REGISTERS as fp16 and fed straight to v_mfma_f32_32x32x16_f16;
+// it never goes through LDS or HBM.
+//
+// Work split.  A workgroup (4 wavefronts) owns 32*MW rows x 256 columns x a K slice; wavefront w
+// owns column tile 4*blockIdx.x + w (lane <-> column, the same records the GEMV reads) and keeps
+// MW x 2 accumulator tiles of 32x32.  The X tile of the current chunk (32*MW rows x 128 k) is
+// staged in LDS once per workgroup, double-buffered, one barrier per chunk.
+//
+// Rebuilding weights.  A lane holds, per plane, the 128 bits of its column for the chunk.  For a
+// 32-bit word w, (w << t) & 0x20002000 isolates bits (pi, pi+16) at bit 13 of the two 16-bit
+// halves: read as packed fp16 that is (2^-7 * b[pi], 2^-7 * b[pi+16]); with mask 0x40004000 (bit 14)
+// it is (2 * b, 2 * b).  One v_pk_fma_f16 per plane with the pre-scaled scale (s * 2^7 or s / 2)
+// adds s_j * b_j for two weights; the chain starts from (z, z).  Cost: 8 shifts + 16 ANDs per
+// word and plane, 16*q packed FMAs per word: about 2.3 VALU lane-ops per weight at q = 2.
+// Precondition of this path: |s_j| < 512 (pre-scaling by 2^7 must stay finite in fp16) -- HLQ
+// scales are weight magnitudes, orders of magnitude below that.
+//
+// Contraction order.  Two weights of a register are k and k+16 of a 32-k block, so the K index
+// runs in the order 0,16,1,17,...,15,31 inside each block; X is written to LDS in the same
+// interleaved order, which makes every A fragment one aligned 16-byte LDS read.  A k-step of the
+// MFMA takes 8 register pairs of a lane: 4 for k-slots 0..7, 4 for slots 8..15.  The matrix core
+// wants slots 0..7 in lanes 0..31 and slots 8..15 in lanes 32..63 for the SAME 32 columns; one
+// v_permlane32_swap per register hands the upper k-slots of columns 0..31 to lanes 32..63 and
+// the lower k-slots of columns 32..63 to lanes 0..31, giving the B operands of both 32-column
+// halves of the tile.
+#include "hlq_internal.h"
+
+namespace {
+
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef _Float16 half8v __attribute__((ext_vector_type(8)));
+typedef float float16v __attribute__((ext_vector_type(16)));
+typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_f32)
+{
+    if (out_f32) ((float *)y)[idx] = v;
+    else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
+}
+
+constexpr int XROW = 128 + 8;   // halfs per staged X row: 128 k + 16 bytes of padding (bank spread)
+
+template <int Q, int G>
+struct WRegs {
+    static constexpr int GS = G < 128 ? G : 128;
+    static constexpr int SEG = 128 / GS;
+    uint32_t w[Q][4];
+    uint16_t mt[SEG][Q + 1];
+};
+
+// position (13 or 14) and left shift that bring pair pi of a word to that position; pair 15 is
+// reached with a right shift by one instead (shift = -1)
+__host__ __device__ constexpr int pair_pos(int pi) { return pi == 15 ? 14 : (pi == 0 ? 14 : (pi % 2 == 1 ? 13 : 14)); }
+__host__ __device__ constexpr int pair_shift(int pi) { return pi == 15 ? -1 : pair_pos(pi) - pi; }
+
+template <int Q, int G, int MW>
+__global__ void __launch_bounds__(256)
+hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const uint16_t *__restrict__ X, long ldx,
+                     int M, void *__restrict__ Y, long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks,
+                     int cps, int nslices, int out_f32)
+{
+    using Regs = WRegs<Q, G>;
+    constexpr int GS = Regs::GS, SEG = Regs::SEG;
+    constexpr int ROWS = 32 * MW;
+    extern __shared__ __attribute__((aligned(16))) _Float16 Xs[];   // [2][ROWS][XROW]
+
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6, lane = tid & 63;
+    const int tile = blockIdx.x * 4 + wave;
+    const int tile_c = tile < ntiles ? tile : ntiles - 1;          // clamped: loads stay in bounds
+    const int tw = hlq_tile_width(tile_c, N);
+    const bool col_ok = tile < ntiles && lane < tw;
+    const int lane_c = lane < tw ? lane : tw - 1;
+    const char *tile_base = packed + (size_t)tile_c * HLQ_TILE_N * col_bytes;
+    const int m0 = blockIdx.z * ROWS;
+    const int cbeg = blockIdx.y * cps;
+    const int cend = min(cbeg + cps, nchunks);
+
+    auto load_w = [&](int c, Regs &R) {
+        const char *rec = tile_base + (size_t)tw * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const uint4 v = ((const uint4 *)rec)[j * tw + lane_c];
+            R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
+        }
+        const char *mrec = rec;
+        if (G > 128) {
+            const int c0 = c & ~1;
+            mrec = tile_base + (size_t)tw * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
+        }
+        const uint16_t *m = (const uint16_t *)(mrec + (size_t)tw * Q * 16);
+#pragma unroll
+        for (int sg = 0; sg < SEG; ++sg)
+#pragma unroll
+            for (int r = 0; r <= Q; ++r) R.mt[sg][r] = m[(sg * (Q + 1) + r) * tw + lane_c];
+    };
+
+    // X staging: item (row, 32-k block d) = 64 contiguous bytes of X, written to LDS with the two
+    // 16-k halves of the block interleaved element-wise.  ROWS*4 items, 256 lanes.
+    constexpr int ITEMS = (ROWS * 4 + 255) / 256;
+    uint4 xreg[ITEMS][4];
+    auto load_x = [&](int c) {
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int item = tid + it * 256;
+            const int row = item >> 2, d = item & 3;
+            const int m = m0 + row;
+            const bool ok = item < ROWS * 4 && m < M;
+            const uint4 *src = (const uint4 *)(X + (size_t)(ok ? m : 0) * ldx + (size_t)c * 128 + d * 32);
+#pragma unroll
+            for (int v = 0; v < 4; ++v) xreg[it][v] = ok ? src[v] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    };
+    auto store_x = [&](int buf) {
+#pragma unroll
+        for (int it = 0; it < ITEMS; ++it) {
+            const int item = tid + it * 256;
+            if (item >= ROWS * 4) continue;
+            const int row = item >> 2, d = item & 3;
+            uint4 *dst = (uint4 *)(Xs + ((size_t)buf * ROWS + row) * XROW + d * 32);
+            // halves h = 0, 1 of the block: elements 8h..8h+7 (register h) and 16+8h.. (register 2+h)
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t a[4] = {xreg[it][h].x, xreg[it][h].y, xreg[it][h].z, xreg[it][h].w};
+                const uint32_t b[4] = {xreg[it][2 + h].x, xreg[it][2 + h].y, xreg[it][2 + h].z, xreg[it][2 + h].w};
+                uint32_t o[8];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    o[2 * i] = (a[i] & 0xffffu) | (b[i] << 16);           // (x[2i],   x[16+2i])
+                    o[2 * i + 1] = (a[i] >> 16) | (b[i] & 0xffff0000u);  // (x[2i+1], x[17+2i])
+                }
+                dst[2 * h] = make_uint4(o[0], o[1], o[2], o[3]);
+                dst[2 * h + 1] = make_uint4(o[4], o[5], o[6], o[7]);
+            }
+        }
+    };
+
+    float16v acc[MW][2];
+#pragma unroll
+    for (int mb = 0; mb < MW; ++mb)
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mb][cb][r] = 0.f;
+
+    const _Float16 *xrow = Xs + (size_t)(lane & 31) * XROW + (lane >> 5) * 8;   // this lane's A-fragment origin
+
+    auto compute = [&](const Regs &R, int buf) {
+        const _Float16 *xb = xrow + (size_t)buf * ROWS * XROW;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            constexpr int dummy = 0;
+            (void)dummy;
+            const int sg = (d * 32) / GS;
+            // pre-scaled scales of this segment as packed pairs: bit 13 reads as 2^-7, bit 14 as 2
+            half2v z2, s13[Q], s14[Q];
+            {
+                const _Float16 z = __builtin_bit_cast(_Float16, R.mt[sg][Q]);
+                z2 = (half2v){z, z};
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const _Float16 s = __builtin_bit_cast(_Float16, R.mt[sg][j]);
+                    const _Float16 a = s * (_Float16)128.0f, b = s * (_Float16)0.5f;
+                    s13[j] = (half2v){a, a};
+                    s14[j] = (half2v){b, b};
+                }
+            }
+            uint32_t wp[16];   // rebuilt weights, register pi = (k = 32d + pi, k = 32d + pi + 16)
+#pragma unroll
+            for (int pi = 0; pi < 16; ++pi) {
+                half2v o = z2;
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const uint32_t wj = R.w[j][d];
+                    const uint32_t sh = pair_shift(pi) < 0 ? (wj >> 1) : (wj << (pair_shift(pi) < 0 ? 0 : pair_shift(pi)));
+                    const uint32_t m = sh & (pair_pos(pi) == 13 ? 0x20002000u : 0x40004000u);
+                    o = __builtin_bit_cast(half2v, m) * (pair_pos(pi) == 13 ? s13[j] : s14[j]) + o;
+                }
+                wp[pi] = __builtin_bit_cast(uint32_t, o);
+            }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {   // two k-steps of 16 per 32-k block
+                uint32_t lo[4], hi[4];
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const uint2v r = __builtin_amdgcn_permlane32_swap(wp[ks * 8 + v], wp[ks * 8 + 4 + v], false, false);
+                    lo[v] = r.x;   // columns 0..31 of the tile:  lanes 0..31 slots 0..7, lanes 32..63 slots 8..15
+                    hi[v] = r.y;   // columns 32..63
+                }
+                half8v b0, b1;
+                {
+                    uint32_t *p0 = (uint32_t *)&b0, *p1 = (uint32_t *)&b1;
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) { p0[v] = lo[v]; p1[v] = hi[v]; }
+                }
+#pragma unroll
+                for (int mb = 0; mb < MW; ++mb) {
+                    const half8v a = *(const half8v *)(xb + (size_t)mb * 32 * XROW + d * 32 + ks * 16);
+                    acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b0, acc[mb][0], 0, 0, 0);
+                    acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b1, acc[mb][1], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    // ---- chunk loop: X double-buffered in LDS, weights of chunk c+1 and X of chunk c+1 prefetched ----
+    if (cbeg < cend) {
+        Regs RA, RB;
+        load_w(cbeg, RA);
+        load_x(cbeg);
+        store_x(0);
+        load_w(min(cbeg + 1, cend - 1), RB);
+        for (int c = cbeg; c < cend; c += 2) {
+            __syncthreads();
+            if (c + 1 < cend) load_x(c + 1);
+            compute(RA, 0);
+            load_w(min(c + 2, cend - 1), RA);
+            if (c + 1 < cend) {
+                store_x(1);
+                __syncthreads();
+                if (c + 2 < cend) load_x(c + 2);
+                compute(RB, 1);
+                load_w(min(c + 3, cend - 1), RB);
+                if (c + 2 < cend) store_x(0);
+            }
+        }
+    }
+
+    // ---- store: D tile register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 ----------------
+#pragma unroll
+    for (int mb = 0; mb < MW; ++mb) {
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+            const int col_in_tile = cb * 32 + (lane & 31);
+            const int n = tile * HLQ_TILE_N + col_in_tile;
+            const bool ok = tile < ntiles && col_in_tile < tw;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int m = m0 + mb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                if (ok && m < M) {
+                    if (nslices == 1) store_out(Y, (size_t)m * ldy + n, acc[mb][cb][r], out_f32);
+                    else ws[((size_t)blockIdx.y * M + m) * N + n] = acc[mb][cb][r];
+                }
+            }
+        }
+    }
+    (void)col_ok;
+}
+
+__global__ void __launch_bounds__(256)
+hlq_gemm_mfma_reduce_kernel(const float *__restrict__ ws, void *__restrict__ Y, long ldy, int M, int N,
+                            int nslices, int out_f32)
+{
+    const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)M * N;
+    if (i >= total) return;
+    float a = 0.f;
+    for (int s = 0; s < nslices; ++s) a += ws[(size_t)s * total + i];
+    const size_t m = i / N, n = i % N;
+    store_out(Y, m * ldy + n, a, out_f32);
+}
+
+struct MfmaPlan {
+    int MW, cps, nslices, rowblocks;
+};
+
+MfmaPlan plan_mfma(const HlqDims &dm, int64_t M)
+{
+    MfmaPlan p;
+    p.MW = M > 64 ? 4 : (M > 32 ? 2 : 1);
+    p.rowblocks = (int)((M + 32 * p.MW - 1) / (32 * p.MW));
+    const long colgroups = (dm.ntiles + 3) / 4;
+    const long wgs = colgroups * p.rowblocks;
+    long want = (512 + wgs - 1) / wgs;                   // K slices wanted to cover the CUs twice
+    const long max_slices = (dm.nchunks + 3) / 4;        // at least 4 chunks per slice
+    if (want > max_slices) want = max_slices;
+    if (want < 1) want = 1;
+    int cps = (int)((dm.nchunks + want - 1) / want);
+    cps = (cps + 1) & ~1;
+    p.cps = cps;
+    p.nslices = (dm.nchunks + cps - 1) / cps;
+    return p;
+}
+
+template <int Q, int G, int MW>
+void launch_one(const HlqDims &dm, const MfmaPlan &p, const char *packed, const uint16_t *X, long ldx, int M,
+                void *Y, long ldy, float *ws, int out_f32, hipStream_t st)
+{
+    const dim3 grid((unsigned)((dm.ntiles + 3) / 4), (unsigned)p.nslices, (unsigned)p.rowblocks);
+    const size_t lds = (size_t)2 * 32 * MW * XROW * sizeof(_Float16);
+    hlq_gemm_mfma_kernel<Q, G, MW><<<grid, 256, lds, st>>>(packed, dm.col_bytes, X, ldx, M, Y, ldy, ws, dm.N, dm.ntiles,
+                                                          dm.nchunks, p.cps, p.nslices, out_f32);
+}
+
+template <int Q, int G>
+void launch_qg(const HlqDims &dm, const MfmaPlan &p, const char *packed, const uint16_t *X, long ldx, int M,
+               void *Y, long ldy, float *ws, int out_f32, hipStream_t st)
+{
+    switch (p.MW) {
+    case 1: launch_one<Q, G, 1>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); break;
+    case 2: launch_one<Q, G, 2>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); break;
+    default: launch_one<Q, G, 4>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); break;
+    }
+}
+
+template <int Q>
+hlq_status launch_q(const HlqDims &dm, const MfmaPlan &p, const char *packed, const uint16_t *X, long ldx, int M,
+                    void *Y, long ldy, float *ws, int out_f32, hipStream_t st)
+{
+    switch (dm.G) {
+    case 32: launch_qg<Q, 32>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    case 64: launch_qg<Q, 64>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    case 128: launch_qg<Q, 128>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    case 256: launch_qg<Q, 256>(dm, p, packed, X, ldx, M, Y, ldy, ws, out_f32, st); return HLQ_OK;
+    }
+    return HLQ_ERR_UNSUPPORTED;
+}
+
+} // namespace
+
+size_t hlq_gemm_mfma_partial_bytes(const HlqDims &dm, int64_t M)
+{
+    const MfmaPlan p = plan_mfma(dm, M);
+    return p.nslices > 1 ? (size_t)p.nslices * (size_t)M * (size_t)dm.N * sizeof(float) : 0;
+}
+
+hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
+                                void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
+{
+    hlq_clear_stale_error();
+    const MfmaPlan p = plan_mfma(dm, M);
+    if (p.rowblocks > 65535) return HLQ_ERR_UNSUPPORTED;
+    const int out_f32 = out == HLQ_OUT_F32;
+    float *part = (float *)((char *)ws + HLQ_WS_COUNTER_BYTES);
+    hlq_status s;
+    switch (dm.q) {
+    case 1: s = launch_q<1>(dm, p, (const char *)packed, X, (long)ldx, (int)M, Y, (long)ldy, part, out_f32, st); break;
+    case 2: s = launch_q<2>(dm, p, (const char *)packed, X, (long)ldx, (int)M, Y, (long)ldy, part, out_f32, st); break;
+    case 3: s = launch_q<3>(dm, p, (const char *)packed, X, (long)ldx, (int)M, Y, (long)ldy, part, out_f32, st); break;
+    case 4: s = launch_q<4>(dm, p, (const char *)packed, X, (long)ldx, (int)M, Y, (long)ldy, part, out_f32, st); break;
+    default: return HLQ_ERR_UNSUPPORTED;
+    }
+    if (s != HLQ_OK) return s;
+    if (p.nslices > 1) {
+        const size_t total = (size_t)M * dm.N;
+        hlq_gemm_mfma_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part, Y, (long)ldy, (int)M, dm.N,
+                                                                                    p.nslices, out_f32);
+    }
+    return hlq_hip_status(hipGetLastError());
+}

@@ -93,6 +93,13 @@ hlq_status hlq_gemv_plan_override(int tn, int w, int cpw);
 #define HLQ_WS_COUNTER_BYTES 131072
 size_t hlq_gemv_partial_bytes(const HlqDims &dm);
 size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M);
+size_t hlq_gemm_lut_partial_bytes(const HlqDims &dm, int64_t M);
+size_t hlq_gemm_mfma_partial_bytes(const HlqDims &dm, int64_t M);
+hlq_status hlq_launch_gemm_lut(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
+                               int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
+hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
+                                int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
+hlq_status hlq_gemm_path_override(int path);
 
 // HLQ_VERBOSE=1 in the environment prints the runtime's message for a failed launch to stderr.
 static inline hlq_status hlq_hip_status(hipError_t e)

@@ -1,0 +1,60 @@
+"""The matrix-core formulation of hlq_lut_gemm against the oracle: row-block sizes, ragged M, N and
+K slices, every (q, G), and agreement with the table-lookup formulation."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import c_oracle
+from oracle import hlq_oracle as O
+from paper_2510_19482_amd import binding as B
+from paper_2510_19482_amd import synth
+
+from gpu_util import TOL, dev, gemm_gpu, pack_on_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def mfma_path():
+    B.set_gemm_path(B.GEMM_MFMA)
+    yield
+    B.set_gemm_path(B.GEMM_AUTO)
+
+
+@pytest.mark.parametrize("M", [2, 17, 32, 33, 64, 65, 100, 128, 200])
+@pytest.mark.parametrize("q,G", [(2, 128), (3, 128), (4, 64), (1, 32), (2, 256)])
+def test_mfma_vs_oracle(M, q, G):
+    K, N = 1280, 584          # 10 chunks; 9 full tiles + a 8-column tail; 3 column groups
+    print("mfma", M, q, G, flush=True)
+    codes, S, Z = synth.make_weight(K, N, q, G, "mfma")
+    X = synth.make_x(M, K, "mfma", outliers=True)
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    ref = c_oracle.gemm_f64(X, codes, S, Z, q, G)
+    Y = gemm_gpu(d, packed, X, out_f32=True)
+    err = O.row_rel_err(Y, ref)
+    assert err.max() <= 1e-3, err.max()
+    Y16 = gemm_gpu(d, packed, X, out_f32=False)
+    assert O.row_rel_err(Y16, ref).max() <= TOL
+
+
+def test_mfma_identity_rows_read_back_weights():
+    # X = rows of the identity: Y[m, :] = W^[k_m, :] rounded to fp16 -- checks the contraction order,
+    # the lane exchange and the output layout entry by entry
+    K, N, q, G = 256, 128, 2, 128
+    codes, S, Z = synth.make_weight(K, N, q, G, "mfma-id")
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    W = O.dequantize(codes, S, Z, q, G)
+    X = np.eye(K, dtype=np.float16)
+    Y = gemm_gpu(d, packed, X, out_f32=True)
+    np.testing.assert_allclose(Y, W, rtol=2e-3, atol=1e-6)
+
+
+def test_mfma_equals_lut_path_within_tolerance():
+    M, K, N, q, G = 48, 2048, 1032, 2, 128
+    codes, S, Z = synth.make_weight(K, N, q, G, "mfma-lut")
+    X = synth.make_x(M, K, "mfma-lut", outliers=True)
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    a = gemm_gpu(d, packed, X, out_f32=True)
+    B.set_gemm_path(B.GEMM_LUT)
+    b = gemm_gpu(d, packed, X, out_f32=True)
+    assert O.row_rel_err(a, b).max() <= 1e-3

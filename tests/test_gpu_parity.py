@@ -116,8 +116,15 @@ def test_gemm_vs_oracle(M, q, G):
     X = synth.make_x(M, K, "gemm", outliers=True)
     d, packed = pack_on_gpu(codes, S, Z, q, G)
     ref = O.gemm_dequant(X, codes, S, Z, q, G)
-    Y = gemm_gpu(d, packed, X, out_f32=True)
-    assert O.row_rel_err(Y, ref).max() <= 2e-5
+    try:
+        B.set_gemm_path(B.GEMM_LUT)           # table lookups: fp32 tables and sums
+        Y = gemm_gpu(d, packed, X, out_f32=True)
+        assert O.row_rel_err(Y, ref).max() <= 2e-5
+        B.set_gemm_path(B.GEMM_MFMA)          # matrix cores: W^ rounded to fp16
+        Y = gemm_gpu(d, packed, X, out_f32=True)
+        assert O.row_rel_err(Y, ref).max() <= 1e-3
+    finally:
+        B.set_gemm_path(B.GEMM_AUTO)
     Y = gemm_gpu(d, packed, X, out_f32=False)
     assert O.row_rel_err(Y, ref).max() <= TOL
 
@@ -130,12 +137,18 @@ def test_gemm_leading_dimensions():
     Xbig = torch.zeros((M, K + 64), dtype=torch.float16, device="cuda")
     Xbig[:, :K] = dev(X)
     Ybig = torch.full((M, N + 24), -5.0, dtype=torch.float32, device="cuda")
-    B.hlq_lut_gemm(d, packed, Xbig[:, :K], Y=Ybig[:, :N], out_f32=True)
-    torch.cuda.synchronize()
-    out = Ybig.cpu().numpy().astype(np.float64)
-    assert np.all(out[:, N:] == -5.0)
     ref = O.gemm_dequant(X, codes, S, Z, q, G)
-    assert O.row_rel_err(out[:, :N], ref).max() <= 2e-5
+    try:
+        for path, tol in ((B.GEMM_LUT, 2e-5), (B.GEMM_MFMA, 1e-3)):
+            B.set_gemm_path(path)
+            Ybig.fill_(-5.0)
+            B.hlq_lut_gemm(d, packed, Xbig[:, :K], Y=Ybig[:, :N], out_f32=True)
+            torch.cuda.synchronize()
+            out = Ybig.cpu().numpy().astype(np.float64)
+            assert np.all(out[:, N:] == -5.0)
+            assert O.row_rel_err(out[:, :N], ref).max() <= tol, path
+    finally:
+        B.set_gemm_path(B.GEMM_AUTO)
 
 
 def test_gemm_m1_equals_gemv():
