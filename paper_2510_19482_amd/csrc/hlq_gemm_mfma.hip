@@ -37,6 +37,7 @@ typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef _Float16 half8v __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 typedef unsigned uint2v __attribute__((ext_vector_type(2)));
+typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_f32)
 {
@@ -60,7 +61,7 @@ __host__ __device__ constexpr int pair_pos(int pi) { return pi == 15 ? 14 : (pi 
 __host__ __device__ constexpr int pair_shift(int pi) { return pi == 15 ? -1 : pair_pos(pi) - pi; }
 
 template <int Q, int G, int MW>
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const uint16_t *__restrict__ X, long ldx,
                      int M, void *__restrict__ Y, long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks,
                      int cps, int nslices, int out_f32)
@@ -186,19 +187,16 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
             }
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {   // two k-steps of 16 per 32-k block
-                uint32_t lo[4], hi[4];
+                // after the exchange: lo = B operand of columns 0..31 of the tile (lanes 0..31 hold
+                // k-slots 0..7, lanes 32..63 slots 8..15), hi = B operand of columns 32..63
+                uint4v lo, hi;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     const uint2v r = __builtin_amdgcn_permlane32_swap(wp[ks * 8 + v], wp[ks * 8 + 4 + v], false, false);
-                    lo[v] = r.x;   // columns 0..31 of the tile:  lanes 0..31 slots 0..7, lanes 32..63 slots 8..15
-                    hi[v] = r.y;   // columns 32..63
+                    lo[v] = r.x;
+                    hi[v] = r.y;
                 }
-                half8v b0, b1;
-                {
-                    uint32_t *p0 = (uint32_t *)&b0, *p1 = (uint32_t *)&b1;
-#pragma unroll
-                    for (int v = 0; v < 4; ++v) { p0[v] = lo[v]; p1[v] = hi[v]; }
-                }
+                const half8v b0 = __builtin_bit_cast(half8v, lo), b1 = __builtin_bit_cast(half8v, hi);
 #pragma unroll
                 for (int mb = 0; mb < MW; ++mb) {
                     const half8v a = *(const half8v *)(xb + (size_t)mb * 32 * XROW + d * 32 + ks * 16);
@@ -233,23 +231,30 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
     }
 
     // ---- store: D tile register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 ----------------
-#pragma unroll
-    for (int mb = 0; mb < MW; ++mb) {
+    if (tile >= ntiles) return;
+    const int rbase = m0 + 4 * (lane >> 5);
+    const bool rows_full = m0 + ROWS <= M;
+    auto store_tiles = [&](auto *dst, long rstride) {   // dst points at (row rbase, column 0 of the tile)
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
             const int col_in_tile = cb * 32 + (lane & 31);
-            const int n = tile * HLQ_TILE_N + col_in_tile;
-            const bool ok = tile < ntiles && col_in_tile < tw;
+            if (col_in_tile >= tw) continue;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int m = m0 + mb * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                if (ok && m < M) {
-                    if (nslices == 1) store_out(Y, (size_t)m * ldy + n, acc[mb][cb][r], out_f32);
-                    else ws[((size_t)blockIdx.y * M + m) * N + n] = acc[mb][cb][r];
+            for (int rr = 0; rr < 4; ++rr) {
+                auto *p = dst + col_in_tile + (long)rr * rstride;
+#pragma unroll
+                for (int blk = 0; blk < 4 * MW; ++blk) {   // rows rbase + rr + 8*blk
+                    const float v = acc[blk >> 2][cb][(blk & 3) * 4 + rr];
+                    if (rows_full || rbase + rr + 8 * blk < M) *p = (decltype(*p + 0))v;
+                    p += 8 * rstride;
                 }
             }
         }
-    }
+    };
+    const size_t n0 = (size_t)tile * HLQ_TILE_N;
+    if (nslices > 1) store_tiles(ws + ((size_t)blockIdx.y * M + rbase) * (size_t)N + n0, (long)N);
+    else if (out_f32) store_tiles((float *)Y + (size_t)rbase * ldy + n0, ldy);
+    else store_tiles((_Float16 *)Y + (size_t)rbase * ldy + n0, ldy);
     (void)col_ok;
 }
 
