@@ -22,8 +22,8 @@
  *   - Supported descriptors: 1 <= q <= 4, G in {32, 64, 128, 256}, K % 128 == 0,
  *     K % G == 0, N % 8 == 0, K, N >= 1, layout == hlq_layout_version()
  *     (anything else: HLQ_ERR_BAD_DESC); K <= 2^21 and N <= 2^20 (beyond: HLQ_ERR_UNSUPPORTED).
- *   - Alignment: packed blobs and workspaces 16 bytes, activations 8 bytes, outputs their
- *     element size; ldx a multiple of 4 when M > 1 (violations: HLQ_ERR_BAD_STRIDE).
+ *   - Alignment: packed blobs, workspaces and activations 16 bytes, outputs their element
+ *     size; ldx a multiple of 8 when M > 1 (violations: HLQ_ERR_BAD_STRIDE).
  */
 #ifndef HLQ_H
 #define HLQ_H

@@ -5,7 +5,7 @@
 hlq_status hlq_check_desc(const hlq_desc *d, HlqDims *out)
 {
     if (!d) return HLQ_ERR_NULL;
-    if (d->layout != HLQ_LAYOUT_V2) return HLQ_ERR_BAD_DESC;
+    if (d->layout != HLQ_LAYOUT_V3) return HLQ_ERR_BAD_DESC;
     if (d->q < 1 || d->q > 4) return HLQ_ERR_BAD_DESC;
     if (d->G != 32 && d->G != 64 && d->G != 128 && d->G != 256) return HLQ_ERR_BAD_DESC;
     if (d->K < 1 || d->N < 1) return HLQ_ERR_BAD_DESC;
@@ -57,7 +57,7 @@ const char *hlq_status_string(hlq_status s)
     return "unknown status";
 }
 
-uint32_t hlq_layout_version(void) { return HLQ_LAYOUT_V2; }
+uint32_t hlq_layout_version(void) { return HLQ_LAYOUT_V3; }
 
 hlq_status hlq_packed_bytes(const hlq_desc *d, size_t *total, size_t *bits, size_t *meta)
 {
@@ -141,7 +141,7 @@ hlq_status hlq_lut_gemv(const hlq_desc *d, const void *packed, const uint16_t *x
     if (s != HLQ_OK) return s;
     if (!packed || !x || !y || !ws) return HLQ_ERR_NULL;
     if (out != HLQ_OUT_F16 && out != HLQ_OUT_F32) return HLQ_ERR_UNSUPPORTED;
-    if (misaligned(packed, 16) || misaligned(x, 8) || misaligned(ws, 16) || misaligned(y, out == HLQ_OUT_F32 ? 4 : 2))
+    if (misaligned(packed, 16) || misaligned(x, 16) || misaligned(ws, 16) || misaligned(y, out == HLQ_OUT_F32 ? 4 : 2))
         return HLQ_ERR_BAD_STRIDE;
     if (ws_bytes < HLQ_WS_COUNTER_BYTES + hlq_gemv_partial_bytes(dm)) return HLQ_ERR_BUFFER_TOO_SMALL;
     HlqGemvItem it;
@@ -167,7 +167,7 @@ hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const void *cons
         if (s != HLQ_OK) return s;
         if (descs[i].q != descs[0].q || descs[i].G != descs[0].G) return HLQ_ERR_UNSUPPORTED;
         if (!packed[i] || !x[i] || !y[i]) return HLQ_ERR_NULL;
-        if (misaligned(packed[i], 16) || misaligned(x[i], 8) || misaligned(y[i], out == HLQ_OUT_F32 ? 4 : 2))
+        if (misaligned(packed[i], 16) || misaligned(x[i], 16) || misaligned(y[i], out == HLQ_OUT_F32 ? 4 : 2))
             return HLQ_ERR_BAD_STRIDE;
         items[i].packed = packed[i];
         items[i].x = x[i];
@@ -189,9 +189,9 @@ hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uint16_t *X
     if (out != HLQ_OUT_F16 && out != HLQ_OUT_F32) return HLQ_ERR_UNSUPPORTED;
     if (M == 0) return HLQ_OK;
     if (!packed || !X || !Y || !ws) return HLQ_ERR_NULL;
-    if (misaligned(packed, 16) || misaligned(X, 8) || misaligned(ws, 16) || misaligned(Y, out == HLQ_OUT_F32 ? 4 : 2))
+    if (misaligned(packed, 16) || misaligned(X, 16) || misaligned(ws, 16) || misaligned(Y, out == HLQ_OUT_F32 ? 4 : 2))
         return HLQ_ERR_BAD_STRIDE;
-    if (M > 1 && ldx % 4 != 0) return HLQ_ERR_BAD_STRIDE;   // rows are read as 8-byte words
+    if (M > 1 && ldx % 8 != 0) return HLQ_ERR_BAD_STRIDE;   // rows are read as 16-byte words
     if (ws_bytes < ws_need(dm, M)) return HLQ_ERR_BUFFER_TOO_SMALL;
     if (M == 1) {
         HlqGemvItem it;

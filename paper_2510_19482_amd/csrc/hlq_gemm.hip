@@ -79,15 +79,17 @@ hlq_gemm_lut_kernel(const char *__restrict__ packed, size_t col_bytes,
         __syncthreads();   // readers of the previous step's tables are done
         if (tid < NT * MB) {
             const int r = tid / NT, tl = tid % NT;   // a wavefront builds one row's 64 tables
-            const int k = c0 * 128 + 4 * tl;
+            // table tl = word (tl / 8), 4-bit slice i = tl % 8: the four even (i < 4) or odd (i >= 4)
+            // activations of the 8-k window 4 * (tl / 8) + (i & 3)
+            const int wnd = 4 * (tl >> 3) + (tl & 3), par = (tl >> 2) & 1;
+            const int k = c0 * 128 + 8 * wnd;
             const int m = m0 + r;
             float xv[4] = {0.f, 0.f, 0.f, 0.f};
             if (m < M && k < cend * 128) {
-                const uint2 raw = *(const uint2 *)(X + (size_t)m * ldx + k);
-                xv[0] = h2f((uint16_t)(raw.x & 0xffffu));
-                xv[1] = h2f((uint16_t)(raw.x >> 16));
-                xv[2] = h2f((uint16_t)(raw.y & 0xffffu));
-                xv[3] = h2f((uint16_t)(raw.y >> 16));
+                const uint4 raw = *(const uint4 *)(X + (size_t)m * ldx + k);
+                const uint32_t xd[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+                for (int v = 0; v < 4; ++v) xv[v] = h2f((uint16_t)(xd[v] >> (16 * par)));
             }
             float e[16];
             e[0] = 0.f;

@@ -12,23 +12,23 @@
 // MW x 2 accumulator tiles of 32x32.  The X tile of the current chunk (32*MW rows x 128 k) is
 // staged in LDS once per workgroup, double-buffered, one barrier per chunk.
 //
-// Rebuilding weights.  A lane holds, per plane, the 128 bits of its column for the chunk.  For a
-// 32-bit word w, (w << t) & 0x20002000 isolates bits (pi, pi+16) at bit 13 of the two 16-bit
-// halves: read as packed fp16 that is (2^-7 * b[pi], 2^-7 * b[pi+16]); with mask 0x40004000 (bit 14)
-// it is (2 * b, 2 * b).  One v_pk_fma_f16 per plane with the pre-scaled scale (s * 2^7 or s / 2)
-// adds s_j * b_j for two weights; the chain starts from (z, z).  Cost: 8 shifts + 16 ANDs per
-// word and plane, 16*q packed FMAs per word: about 2.3 VALU lane-ops per weight at q = 2.
+// Rebuilding weights.  A lane holds, per plane, the 128 bits of its column for the chunk; in a
+// 32-bit plane word bits p and p+16 are the adjacent weights k0 = 2p, 2p+1 of the word's 32-k
+// block.  (w << t) & 0x20002000 isolates such a pair at bit 13 of the two 16-bit halves: read as
+// packed fp16 that is (2^-7 * b[2p], 2^-7 * b[2p+1]); with mask 0x40004000 (bit 14) it is
+// (2 * b, 2 * b).  One v_pk_fma_f16 per plane with the pre-scaled scale (s * 2^7 or s / 2) adds
+// s_j * b_j for two weights; the chain starts from (z, z).  Cost: 8 shifts + 16 ANDs per word and
+// plane, 16*q packed FMAs per word: about 2.3 VALU lane-ops per weight at q = 2.
 // Precondition of this path: |s_j| < 512 (pre-scaling by 2^7 must stay finite in fp16) -- HLQ
 // scales are weight magnitudes, orders of magnitude below that.
 //
-// Contraction order.  Two weights of a register are k and k+16 of a 32-k block, so the K index
-// runs in the order 0,16,1,17,...,15,31 inside each block; X is written to LDS in the same
-// interleaved order, which makes every A fragment one aligned 16-byte LDS read.  A k-step of the
-// MFMA takes 8 register pairs of a lane: 4 for k-slots 0..7, 4 for slots 8..15.  The matrix core
-// wants slots 0..7 in lanes 0..31 and slots 8..15 in lanes 32..63 for the SAME 32 columns; one
-// v_permlane32_swap per register hands the upper k-slots of columns 0..31 to lanes 32..63 and
-// the lower k-slots of columns 32..63 to lanes 0..31, giving the B operands of both 32-column
-// halves of the tile.
+// Contraction order.  Register pair p of a word holds k0 = 2p, 2p+1, so registers 8ks .. 8ks+7
+// hold the 16 consecutive k of k-step ks in natural order and every A fragment is one aligned
+// 16-byte LDS read of the staged X tile.  A k-step of the MFMA takes 8 registers of a lane: 4
+// for k-slots 0..7, 4 for slots 8..15.  The matrix core wants slots 0..7 in lanes 0..31 and slots
+// 8..15 in lanes 32..63 for the SAME 32 columns; one v_permlane32_swap per register hands the
+// upper k-slots of columns 0..31 to lanes 32..63 and the lower k-slots of columns 32..63 to
+// lanes 0..31, giving the B operands of both 32-column halves of the tile.
 #include "hlq_internal.h"
 
 namespace {
@@ -102,8 +102,8 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
             for (int r = 0; r <= Q; ++r) R.mt[sg][r] = m[(sg * (Q + 1) + r) * tw + lane_c];
     };
 
-    // X staging: item (row, 32-k block d) = 64 contiguous bytes of X, written to LDS with the two
-    // 16-k halves of the block interleaved element-wise.  ROWS*4 items, 256 lanes.
+    // X staging: item (row, 32-k block d) = 64 contiguous bytes of X, copied to LDS as they are.
+    // ROWS*4 items, 256 lanes.
     constexpr int ITEMS = (ROWS * 4 + 255) / 256;
     uint4 xreg[ITEMS][4];
     auto load_x = [&](int c) {
@@ -125,20 +125,8 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
             if (item >= ROWS * 4) continue;
             const int row = item >> 2, d = item & 3;
             uint4 *dst = (uint4 *)(Xs + ((size_t)buf * ROWS + row) * XROW + d * 32);
-            // halves h = 0, 1 of the block: elements 8h..8h+7 (register h) and 16+8h.. (register 2+h)
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t a[4] = {xreg[it][h].x, xreg[it][h].y, xreg[it][h].z, xreg[it][h].w};
-                const uint32_t b[4] = {xreg[it][2 + h].x, xreg[it][2 + h].y, xreg[it][2 + h].z, xreg[it][2 + h].w};
-                uint32_t o[8];
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    o[2 * i] = (a[i] & 0xffffu) | (b[i] << 16);           // (x[2i],   x[16+2i])
-                    o[2 * i + 1] = (a[i] >> 16) | (b[i] & 0xffff0000u);  // (x[2i+1], x[17+2i])
-                }
-                dst[2 * h] = make_uint4(o[0], o[1], o[2], o[3]);
-                dst[2 * h + 1] = make_uint4(o[4], o[5], o[6], o[7]);
-            }
+            for (int v = 0; v < 4; ++v) dst[v] = xreg[it][v];
         }
     };
 
@@ -172,7 +160,7 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
                     s14[j] = (half2v){b, b};
                 }
             }
-            uint32_t wp[16];   // rebuilt weights, register pi = (k = 32d + pi, k = 32d + pi + 16)
+            uint32_t wp[16];   // rebuilt weights, register pi = (k = 32d + 2*pi, k = 32d + 2*pi + 1)
 #pragma unroll
             for (int pi = 0; pi < 16; ++pi) {
                 half2v o = z2;

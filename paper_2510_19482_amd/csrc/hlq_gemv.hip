@@ -73,7 +73,7 @@ struct ChunkRegs {
     static constexpr int SEG = 128 / GS;           // scale segments per chunk
     uint32_t w[TN][Q][4];
     uint16_t mt[TN][SEG][Q + 1];
-    uint2 x;                                       // this lane's four activations (table build)
+    uint4 x;                                       // this lane's 8-k activation window (table build)
 };
 
 // ---- hand-scheduled lookup blocks -----------------------------------------------------------------
@@ -253,8 +253,10 @@ hlq_gemv_kernel(const GemvBatch b)
         tile_base[tn] = P.packed + (size_t)tile_c * HLQ_TILE_N * P.col_bytes;
     }
 
-    // table-build role of this lane: entries 8h .. 8h+7 of table t of the current chunk
-    const int bt = lane >> 1, bh = lane & 1;
+    // table-build role of this lane: 8-k window bw of the chunk, parity bp (even / odd k of the
+    // window, i.e. the table of word bw/4, 4-bit slice (bw & 3) + 4*bp), entries 8*bh .. 8*bh+7
+    const int bw = lane >> 2, bp = (lane >> 1) & 1, bh = lane & 1;
+    const int bt = 8 * (bw >> 2) + (bw & 3) + 4 * bp;
     char *Tw = (char *)lds + wave * HLQ_GEMV_TABLE_BYTES;
     // LDS byte address of this wavefront's tables, a multiple of 256
     const uint32_t tbase = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)Tw;
@@ -281,7 +283,7 @@ hlq_gemv_kernel(const GemvBatch b)
 #pragma unroll
                 for (int r = 0; r <= Q; ++r) R.mt[tn][sg][r] = m[(sg * (Q + 1) + r) * w_ + lane_c[tn]];
         }
-        R.x = *(const uint2 *)(P.x + (size_t)c * 128 + 4 * bt);
+        R.x = *(const uint4 *)(P.x + (size_t)c * 128 + 8 * bw);
     };
 
     float acc[TN];
@@ -289,20 +291,25 @@ hlq_gemv_kernel(const GemvBatch b)
     for (int tn = 0; tn < TN; ++tn) acc[tn] = 0.f;
 
     auto step = [&](const Regs &R) {
-        // build: entries 8h .. 8h+7 of table bt;  entry i = sum_r bit_r(i) x_r  (fp32)
-        const half2_t x01 = __builtin_bit_cast(half2_t, R.x.x), x23 = __builtin_bit_cast(half2_t, R.x.y);
-        const float x0 = (float)x01.x, x1 = (float)x01.y, x2 = (float)x23.x, x3 = (float)x23.y;
-        const float e0 = bh ? x3 : 0.f;
-        const float e1 = e0 + x0, e2 = e0 + x1, e3 = e1 + x1;
+        // build: entries 8h .. 8h+7 of table bt;  entry i = sum_r bit_r(i) x_r  (fp32), where
+        // x_r is the r-th even (bp = 0) or odd (bp = 1) activation of the window
+        const uint32_t xd[4] = {R.x.x, R.x.y, R.x.z, R.x.w};
+        float xv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            xv[r] = (float)__builtin_bit_cast(_Float16, (uint16_t)(xd[r] >> (16 * bp)));
+        const float e0 = bh ? xv[3] : 0.f;
+        const float e1 = e0 + xv[0], e2 = e0 + xv[1], e3 = e1 + xv[1];
         float4 *dst = (float4 *)(Tw + bt * 64 + bh * 32);
         dst[0] = make_float4(e0, e1, e2, e3);
-        dst[1] = make_float4(e0 + x2, e1 + x2, e2 + x2, e3 + x2);
-        // sums of the segments' activations: exact fp32 dot products with (1, 1), then a DPP
-        // reduction over the 16 lanes (8 tables, 32 k) of a row and, for larger groups, over rows
+        dst[1] = make_float4(e0 + xv[2], e1 + xv[2], e2 + xv[2], e3 + xv[2]);
+        // sums of the segments' activations: exact fp32 dot products of the window with (1, 1)
+        // (the four lanes of a quad share a window), then a DPP reduction over the four windows
+        // (32 k) of a 16-lane row and, for larger groups, over rows
         const half2_t ones = {(_Float16)1.0f, (_Float16)1.0f};
-        float tot = __builtin_amdgcn_fdot2(x01, ones, 0.f, false);
-        tot = __builtin_amdgcn_fdot2(x23, ones, tot, false);
-        tot = add_dpp<0x4E>(tot);    // quad_perm [2,3,0,1]: the other table of the quad
+        float tot = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tot = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, xd[r]), ones, tot, false);
         tot = add_dpp<0x124>(tot);   // row_ror:4
         tot = add_dpp<0x128>(tot);   // row_ror:8   -> every lane holds its row's 32-k sum
         float xs[SEG];

@@ -10,7 +10,7 @@
 #include "hlq.h"
 
 // ---------------------------------------------------------------------------------------
-// Packed layout "HLQ2" (designed for 128-bit coalesced loads by 64-wide wavefronts):
+// Packed layout "HLQ3" (designed for 128-bit coalesced loads by 64-wide wavefronts):
 //
 // The matrix is cut into column tiles of 64 columns (the last tile holds N - 64*tile
 // columns, a multiple of 8) and into chunks of 128 consecutive k.  Everything one
@@ -26,14 +26,20 @@
 //                                                      chunk c (s = their index in the chunk):
 //                                                      r < q scale s_r[g, n], r == q zero z[g, n]
 //
-//   The 16 bytes of (plane j, lane) are four little-endian 32-bit words; bit b of word d is
-//   the plane-j bit of weight (k = 128c + 32d + b, n = 64*tile + lane).  A 4-bit slice
-//   [4i+3:4i] of word d is thus the table index for activations k = 128c + 32d + 4i .. +3
-//   (bit r <-> k + r).  With G = 256 a group spans two chunks; its meta sits in the even one.
+//   The 16 bytes of (plane j, lane) are four little-endian 32-bit words, word d covering the
+//   32-k block k = 128c + 32d .. +31 of column n = 64*tile + lane.  Inside a word the even k of
+//   the block sit in the low half and the odd k in the high half: weight k0 (0 <= k0 < 32) is
+//   bit (k0 >> 1) + 16 * (k0 & 1).  Consequences the kernels rely on:
+//     - a 4-bit slice [4i+3:4i] of a word indexes the table of the four activations
+//       k0 = 8*(i & 3) + 2r + (i >> 2), r = 0..3 (bit r <-> r): four even or four odd k of one
+//       8-k window -- any grouping of four activations serves the lookup method;
+//     - bits p and p+16 of a word are the ADJACENT weights k0 = 2p, 2p+1, so one AND with a
+//       two-bit mask yields a packed pair in natural k order for the matrix-core path.
+//   With G = 256 a group spans two chunks; its meta sits in the even one.
 //
 // Total size is exactly K*N*q/8 + 2*(q+1)*(K/G)*N bytes: no padding anywhere.
 // ---------------------------------------------------------------------------------------
-#define HLQ_LAYOUT_V2 0x484c5132u /* "HLQ2" */
+#define HLQ_LAYOUT_V3 0x484c5133u /* "HLQ3" */
 #define HLQ_CHUNK_K 128
 #define HLQ_TILE_N 64
 #define HLQ_MAX_K (1 << 21)
@@ -48,6 +54,9 @@ struct HlqDims {
     size_t bits_bytes;
     size_t meta_bytes;
 };
+
+// bit position inside a plane word of weight k0 (0..31) of the word's 32-k block
+__host__ __device__ __forceinline__ int hlq_bit_pos(int k0) { return (k0 >> 1) + 16 * (k0 & 1); }
 
 // groups whose meta is stored before chunk c of a tile
 __host__ __device__ __forceinline__ int hlq_groups_before(int c, int G) { return (c * HLQ_CHUNK_K + G - 1) / G; }

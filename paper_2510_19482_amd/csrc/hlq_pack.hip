@@ -23,7 +23,7 @@ hlq_pack_bits_kernel(const uint8_t *__restrict__ codes, char *__restrict__ packe
         for (int b = 0; b < 32; ++b) {
             const uint32_t code = src[(size_t)(32 * d + b) * N];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) w[j][d] |= ((code >> j) & 1u) << b;
+            for (int j = 0; j < 4; ++j) w[j][d] |= ((code >> j) & 1u) << hlq_bit_pos(b);
         }
     }
     const int tile = n / HLQ_TILE_N, lane = n % HLQ_TILE_N, tw = hlq_tile_width(tile, N);
@@ -51,7 +51,7 @@ hlq_unpack_bits_kernel(const char *__restrict__ packed, uint8_t *__restrict__ co
         for (int b = 0; b < 32; ++b) {
             uint32_t code = 0u;
 #pragma unroll
-            for (int j = 0; j < 4; ++j) code |= ((w[j][d] >> b) & 1u) << j;
+            for (int j = 0; j < 4; ++j) code |= ((w[j][d] >> hlq_bit_pos(b)) & 1u) << j;
             dst[(size_t)(32 * d + b) * N] = (uint8_t)code;
         }
     }
