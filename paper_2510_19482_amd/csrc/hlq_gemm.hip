@@ -262,20 +262,27 @@ static bool use_mfma(int64_t M)
 {
     if (g_gemm_path == 1) return false;
     if (g_gemm_path == 2) return true;
-    // measured on MI355X (8B shapes, q = 2..4): the lookup kernel wins up to M = 4, from M = 8 on the
-    // matrix-core kernel is faster and the gap grows with M
-    return M >= 8;
+    // measured on MI355X (8B shapes, q = 2..4, HIP-graph timing): the matrix-core kernels are faster
+    // than the lookup kernel from M = 2 on, and the gap grows with M
+    return M >= 2;
 }
 
 size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
 {
-    const size_t a = hlq_gemm_lut_partial_bytes(dm, M), b = hlq_gemm_mfma_partial_bytes(dm, M);
-    return a > b ? a : b;
+    size_t a = hlq_gemm_lut_partial_bytes(dm, M);
+    const size_t b = hlq_gemm_mfma_partial_bytes(dm, M), c = hlq_gemm_skinny_partial_bytes(dm, M);
+    if (b > a) a = b;
+    if (c > a) a = c;
+    return a;
 }
 
 hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
                            void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
 {
-    if (use_mfma(M)) return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
+    if (use_mfma(M)) {
+        // a few rows: GEMV-shaped streaming kernel; many rows: tiled kernel with X staged in LDS
+        if (M <= 32) return hlq_launch_gemm_skinny(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
+        return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
+    }
     return hlq_launch_gemm_lut(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
 }

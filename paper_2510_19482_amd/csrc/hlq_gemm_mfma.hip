@@ -29,15 +29,9 @@
 // 8..15 in lanes 32..63 for the SAME 32 columns; one v_permlane32_swap per register hands the
 // upper k-slots of columns 0..31 to lanes 32..63 and the lower k-slots of columns 32..63 to
 // lanes 0..31, giving the B operands of both 32-column halves of the tile.
-#include "hlq_internal.h"
+#include "hlq_mfma_common.h"
 
 namespace {
-
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
-typedef _Float16 half8v __attribute__((ext_vector_type(8)));
-typedef float float16v __attribute__((ext_vector_type(16)));
-typedef unsigned uint2v __attribute__((ext_vector_type(2)));
-typedef unsigned uint4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_f32)
 {
@@ -54,11 +48,6 @@ struct WRegs {
     uint32_t w[Q][4];
     uint16_t mt[SEG][Q + 1];
 };
-
-// position (13 or 14) and left shift that bring pair pi of a word to that position; pair 15 is
-// reached with a right shift by one instead (shift = -1)
-__host__ __device__ constexpr int pair_pos(int pi) { return pi == 15 ? 14 : (pi == 0 ? 14 : (pi % 2 == 1 ? 13 : 14)); }
-__host__ __device__ constexpr int pair_shift(int pi) { return pi == 15 ? -1 : pair_pos(pi) - pi; }
 
 template <int Q, int G, int MW>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -147,32 +136,13 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
             constexpr int dummy = 0;
             (void)dummy;
             const int sg = (d * 32) / GS;
-            // pre-scaled scales of this segment as packed pairs: bit 13 reads as 2^-7, bit 14 as 2
-            half2v z2, s13[Q], s14[Q];
-            {
-                const _Float16 z = __builtin_bit_cast(_Float16, R.mt[sg][Q]);
-                z2 = (half2v){z, z};
+            HlqSegScales<Q> sc;
+            sc.set(R.mt[sg]);
+            uint32_t wd[Q];
 #pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    const _Float16 s = __builtin_bit_cast(_Float16, R.mt[sg][j]);
-                    const _Float16 a = s * (_Float16)128.0f, b = s * (_Float16)0.5f;
-                    s13[j] = (half2v){a, a};
-                    s14[j] = (half2v){b, b};
-                }
-            }
+            for (int j = 0; j < Q; ++j) wd[j] = R.w[j][d];
             uint32_t wp[16];   // rebuilt weights, register pi = (k = 32d + 2*pi, k = 32d + 2*pi + 1)
-#pragma unroll
-            for (int pi = 0; pi < 16; ++pi) {
-                half2v o = z2;
-#pragma unroll
-                for (int j = 0; j < Q; ++j) {
-                    const uint32_t wj = R.w[j][d];
-                    const uint32_t sh = pair_shift(pi) < 0 ? (wj >> 1) : (wj << (pair_shift(pi) < 0 ? 0 : pair_shift(pi)));
-                    const uint32_t m = sh & (pair_pos(pi) == 13 ? 0x20002000u : 0x40004000u);
-                    o = __builtin_bit_cast(half2v, m) * (pair_pos(pi) == 13 ? s13[j] : s14[j]) + o;
-                }
-                wp[pi] = __builtin_bit_cast(uint32_t, o);
-            }
+            hlq_rebuild_word<Q>(wd, sc, wp);
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {   // two k-steps of 16 per 32-k block
                 // after the exchange: lo = B operand of columns 0..31 of the tile (lanes 0..31 hold

@@ -108,6 +108,9 @@ hlq_status hlq_launch_gemm_lut(const HlqDims &dm, const void *packed, const uint
                                int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
                                 int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
+size_t hlq_gemm_skinny_partial_bytes(const HlqDims &dm, int64_t M);
+hlq_status hlq_launch_gemm_skinny(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
+                                  int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_gemm_path_override(int path);
 
 // HLQ_VERBOSE=1 in the environment prints the runtime's message for a failed launch to stderr.

@@ -49,6 +49,21 @@ def test_mfma_identity_rows_read_back_weights():
     np.testing.assert_allclose(Y, W, rtol=2e-3, atol=1e-6)
 
 
+@pytest.mark.parametrize("M", [3, 16, 29])
+def test_few_rows_one_hot_read_back_weights(M):
+    # one-hot rows through the few-row kernel (M <= 32): checks its lane-group transpose, A-fragment
+    # addressing and output layout entry by entry
+    K, N, q, G = 512, 200, 3, 64
+    codes, S, Z = synth.make_weight(K, N, q, G, "skinny-id")
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    W = O.dequantize(codes, S, Z, q, G)
+    ks = (np.arange(M) * 37 + 5) % K
+    X = np.zeros((M, K), dtype=np.float16)
+    X[np.arange(M), ks] = 1.0
+    Y = gemm_gpu(d, packed, X, out_f32=True)
+    np.testing.assert_allclose(Y, W[ks], rtol=2e-3, atol=1e-6)
+
+
 def test_mfma_equals_lut_path_within_tolerance():
     M, K, N, q, G = 48, 2048, 1032, 2, 128
     codes, S, Z = synth.make_weight(K, N, q, G, "mfma-lut")
