@@ -122,6 +122,14 @@ HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const vo
  * Values outside the ranges above: HLQ_ERR_UNSUPPORTED. */
 HLQ_API hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int chunks_per_wave);
 
+/* Tuning knob (process-wide, not thread-safe): formulation of the per-plane dot products in
+ * hlq_lut_gemv / hlq_lut_gemv_batch.  0 = automatic, 1 = table lookups (App. B), 2 = matrix
+ * cores (plane words expanded to 4-bit floats, activations as an exact sum of four 8-bit
+ * floats; the matrix core keeps 13 bits below the largest product of an 8-element run, so a
+ * result can differ from exact fp32 accumulation by about 1e-4 of the products' magnitude).
+ * Other values: HLQ_ERR_UNSUPPORTED.  Activations must be finite. */
+HLQ_API hlq_status hlq_set_gemv_path(int path);
+
 /* Tuning knob (process-wide, not thread-safe): formulation used by hlq_lut_gemm for M > 1.
  * 0 = automatic (table lookups for small M, matrix cores from the measured crossover on),
  * 1 = table lookups always, 2 = matrix cores always.  Other values: HLQ_ERR_UNSUPPORTED.

@@ -66,6 +66,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_set_gemv_plan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.hlq_set_gemm_path.restype = ctypes.c_int
     lib.hlq_set_gemm_path.argtypes = [ctypes.c_int]
+    lib.hlq_set_gemv_path.restype = ctypes.c_int
+    lib.hlq_set_gemv_path.argtypes = [ctypes.c_int]
     lib.hlq_lut_gemm.restype = ctypes.c_int
     lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     return lib
@@ -100,6 +102,13 @@ GEMM_AUTO, GEMM_LUT, GEMM_MFMA = 0, 1, 2
 
 def set_gemm_path(path: int = 0) -> None:
     _check("hlq_set_gemm_path", lib.hlq_set_gemm_path(path))
+
+
+GEMV_AUTO, GEMV_LUT, GEMV_MX = 0, 1, 2
+
+
+def set_gemv_path(path: int = 0) -> None:
+    _check("hlq_set_gemv_path", lib.hlq_set_gemv_path(path))
 
 
 def packed_bytes(desc: HlqDesc):

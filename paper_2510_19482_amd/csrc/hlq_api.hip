@@ -112,6 +112,8 @@ hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int ch
 
 hlq_status hlq_set_gemm_path(int path) { return hlq_gemm_path_override(path); }
 
+hlq_status hlq_set_gemv_path(int path) { return hlq_gemv_path_override(path); }
+
 hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint16_t *scales,
                     const uint16_t *zeros, void *packed, size_t packed_bytes, void *stream)
 {

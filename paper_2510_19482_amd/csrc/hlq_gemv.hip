@@ -24,35 +24,11 @@
 // the partials in slice order, so the result does not depend on arrival order.
 #include <stdlib.h>
 
-#include "hlq_internal.h"
+#include "hlq_gemv_common.h"
 
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
-
-struct GemvProb {
-    const char *packed;
-    const uint16_t *x;
-    void *y;
-    float *part;       // [nslices][N] partial sums (nslices > 1)
-    int *cnt;          // [ntg] arrival counters, zero between launches
-    size_t col_bytes;
-    int N, nchunks, ntiles, ntg, nslices, cps, blk_begin;
-};
-
-struct GemvBatch {
-    GemvProb p[HLQ_MAX_BATCH];
-    int count;
-    int out_f32;
-};
-
-__device__ __forceinline__ float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
-
-__device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_f32)
-{
-    if (out_f32) ((float *)y)[idx] = v;
-    else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
-}
 
 // v + (v moved across lanes by DPP control CTRL), rows outside ROWMASK unchanged
 template <int CTRL, int ROWMASK = 0xf>
@@ -455,6 +431,15 @@ struct GemvPlan {
 
 // process-wide overrides set by hlq_set_gemv_plan (0 = automatic)
 int g_plan_tn = 0, g_plan_w = 0, g_plan_cpw = 0;
+// formulation: 0 automatic, 1 table lookup, 2 matrix core (hlq_set_gemv_path)
+int g_gemv_path = 0;
+
+bool use_mx()
+{
+    static const int env_path = env_int("HLQ_GEMV_PATH", 0);
+    const int path = g_gemv_path ? g_gemv_path : env_path;
+    return path != 1;   // automatic: the matrix-core kernel is the faster one on every measured shape
+}
 
 GemvPlan plan_gemv(long units)
 {
@@ -468,6 +453,12 @@ GemvPlan plan_gemv(long units)
     pl.TN = 1;
     pl.W = 4;
     pl.cpw = units >= 65536 ? 8 : 4;
+    if (use_mx()) {
+        // matrix-core kernel (sweeps on the same shapes): short runs on many wavefronts while the
+        // launch is small, longer runs once the chip is full
+        pl.W = units < 12000 ? 8 : units < 65536 ? 4 : 8;
+        pl.cpw = units < 12000 ? 4 : 8;
+    }
     if (env_tn) pl.TN = env_tn;
     if (env_w) pl.W = env_w;
     if (env_cpw) pl.cpw = env_cpw;
@@ -482,6 +473,13 @@ int slice_chunks(const GemvPlan &pl) { return (pl.W * pl.cpw + 1) & ~1; }
 int slices_for(const HlqDims &dm, int cps) { return (dm.nchunks + cps - 1) / cps; }
 
 } // namespace
+
+hlq_status hlq_gemv_path_override(int path)
+{
+    if (path < 0 || path > 2) return HLQ_ERR_UNSUPPORTED;
+    g_gemv_path = path;
+    return HLQ_OK;
+}
 
 hlq_status hlq_gemv_plan_override(int tn, int w, int cpw)
 {
@@ -516,13 +514,15 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     long units = 0;
     for (int i = 0; i < count; ++i) units += (long)items[i].dm.ntiles * items[i].dm.nchunks;
     GemvPlan pl = plan_gemv(units);
+    const bool mx = use_mx();
     {
         const int q0 = items[0].dm.q, G0 = items[0].dm.G;
-        if (!gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
-        const int maxw = gemv_max_threads(q0, G0, pl.TN) / 64;
+        if (mx || !gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
+        const int maxw = mx ? hlq_gemv_mx_max_waves(q0, G0) : gemv_max_threads(q0, G0, pl.TN) / 64;
         if (pl.W > maxw) pl.W = maxw;
     }
     if (pl.W < 1 || pl.W > 16 || (pl.TN != 1 && pl.TN != 2) || pl.cpw < 1) return HLQ_ERR_UNSUPPORTED;
+    // chunks per K slice of the lookup kernel: each of its W wavefronts takes cpw chunks of one tile
     int cps = slice_chunks(pl);
     if (cps < 4) cps = 4;
 
@@ -533,12 +533,22 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     float *part = (float *)((char *)ws + HLQ_WS_COUNTER_BYTES);
     long blk = 0;
     long cnt_used = 0;
+    // Workgroups start in block order: problems whose K is split across workgroups go first, so the
+    // extra trips to memory at their end overlap with the other problems' streaming.
+    int order[HLQ_MAX_BATCH];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && slices_for(items[order[j]].dm, cps) > slices_for(items[order[j - 1]].dm, cps); --j) {
+            const int t = order[j];
+            order[j] = order[j - 1];
+            order[j - 1] = t;
+        }
     for (int i = 0; i < count; ++i) {
-        const HlqDims &dm = items[i].dm;
+        const HlqDims &dm = items[order[i]].dm;
         GemvProb &p = b.p[i];
-        p.packed = (const char *)items[i].packed;
-        p.x = items[i].x;
-        p.y = items[i].y;
+        p.packed = (const char *)items[order[i]].packed;
+        p.x = items[order[i]].x;
+        p.y = items[order[i]].y;
         p.col_bytes = dm.col_bytes;
         p.N = dm.N;
         p.nchunks = dm.nchunks;
@@ -560,6 +570,11 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
 
     const int q = items[0].dm.q, G = items[0].dm.G;
     hlq_status s;
+    if (mx) {
+        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, q, G, st);
+        if (s != HLQ_OK) return s;
+        return hlq_hip_status(hipGetLastError());
+    }
     switch (q) {
     case 1: s = launch_q<1>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
     case 2: s = launch_q<2>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;

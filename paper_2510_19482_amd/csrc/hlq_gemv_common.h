@@ -1,0 +1,36 @@
+// Kernel argument block and epilogue pieces shared by the two GEMV formulations (table lookup and
+// matrix core).  Both use the same work split: a workgroup owns one group of column tiles and one
+// K slice, its wavefronts take consecutive K ranges, K slices of different workgroups meet in the
+// workspace.
+#pragma once
+
+#include "hlq_internal.h"
+
+struct GemvProb {
+    const char *packed;
+    const uint16_t *x;
+    void *y;
+    float *part;       // [nslices][N] partial sums (nslices > 1)
+    int *cnt;          // [ntg] arrival counters, zero between launches
+    size_t col_bytes;
+    int N, nchunks, ntiles, ntg, nslices, cps, blk_begin;
+};
+
+struct GemvBatch {
+    GemvProb p[HLQ_MAX_BATCH];
+    int count;
+    int out_f32;
+};
+
+__device__ __forceinline__ float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
+
+__device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_f32)
+{
+    if (out_f32) ((float *)y)[idx] = v;
+    else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
+}
+
+// matrix-core formulation (hlq_gemv_mx.hip): same work split as the lookup kernel with one tile per
+// wavefront (ntg = ntiles)
+hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st);
+int hlq_gemv_mx_max_waves(int q, int G);

@@ -1,0 +1,410 @@
+// hlq_lut_gemv, matrix-core formulation of the bit-serial product (Sec. 2, Eq. 5-6):
+//
+//   y[n] = sum_groups ( sum_j s_j[g,n] * <b_j[.,n], x>_g  +  z[g,n] * sum_g(x) )
+//
+// The inner bit-plane dot product <b_j, x> over a group -- the quantity the lookup tables of App. B
+// deliver four activations at a time -- is taken here by v_mfma_f32_16x16x128_f8f6f4, which
+// multiplies 4-bit by 8-bit floating-point operands:
+//
+//   planes       a 32-bit plane word becomes 32 fp4 (e2m1) values with four AND masks: bit 4p+r of
+//                the word lands in nibble p of register r as the code 1, 2, 4 or 4 (value 0.5, 1,
+//                2, 2).  No table, no LDS traffic, 5 VALU operations per 32 weights.
+//   activations  x (fp16) is written as an exact sum of four bf8 (e5m2) terms, x = t0+t1+t2+t3
+//                (each term is the running remainder rounded to three significant bits, so after
+//                four terms all eleven bits of an fp16 significand are covered), after a power-of-
+//                two weight (1/2, 1/4, 1/8, 1/8 by register r) that evens out the plane codes.  The
+//                four terms occupy four ROWS of the 16-row operand; with quant groups shorter than
+//                a chunk the rows are further split by segment (row 4t + sg holds term t, zero
+//                outside segment sg), so one MFMA returns every (term, segment) dot product of 16
+//                columns x 128 k of one plane.
+//   zero point   the same MFMA with an all-ones plane gives the segment sums of x.
+//
+// The matrix core adds the products of an 8-element run in fixed point aligned to the run's largest
+// product and keeps 13 bits below it (measured); every bf8 x fp4 product has three significant
+// bits, so a product loses bits only if it is more than 2^10 times smaller than its largest
+// neighbour, and then less than 2^-13 of that neighbour.  Everything else is exact fp32 work.
+//
+// Work split (that of the lookup kernel, hlq_gemv.hip).  A workgroup owns one column tile and one K
+// slice; its W wavefronts take W consecutive runs of chunks of the slice and add their results
+// through LDS; slices of different workgroups meet in the workspace (partial sums, one arrival
+// counter per tile, the last workgroup adds in slice order).  Everything up to the final sum is
+// private to the wavefront, so the chunk loop has no barrier:
+//
+//   scale     the largest |x| of the wavefront's run fixes a power-of-two scale that puts the
+//             activations high in the bf8 range; it is removed from the result at the end, so
+//             activations of any magnitude keep their precision;
+//   convert   per chunk, lane l turns x[2l], x[2l+1] into four bf8 terms each and stores the codes
+//             in the wavefront's LDS block in matrix-core k order, one chunk ahead of the MFMAs;
+//   contract  per chunk and column block one MFMA per plane, plus one with the all-ones plane.
+//
+// Lane l loads the four plane words of column l (one 128-bit load per plane, as the lookup kernel
+// does); a 4 x 4 transpose over (16-lane group, word) by v_permlane16_swap / v_permlane32_swap then
+// gives lane l = c + 16 g word g (32 k) of column 16 cb + c for the four column blocks cb -- the
+// plane operand.  As result the lane holds, for column 16 cb + c, the dot products of term g
+// (register = segment).
+#include "hlq_gemv_common.h"
+
+#ifndef HLQ_MX_DEBUG
+#define HLQ_MX_DEBUG 0   // timing experiments -- 1: loads only, 2: no reloads (compute only)
+#endif
+
+namespace {
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
+typedef int int8v __attribute__((ext_vector_type(8)));
+typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+// Rounds the pair v to three significant bits (nearest, ties to even), stores the two bf8 codes at
+// LDS bytes addr + 128 T and addr + 128 T + 4, returns the remainder (exact).  |v| < 61440, so the
+// rounding cannot reach infinity.
+template <int T>
+__device__ __forceinline__ half2_t put_term(uint32_t addr, half2_t v)
+{
+    const uint32_t u = __builtin_bit_cast(uint32_t, v);
+    const uint32_t rnd = u + ((u >> 8) & 0x00010001u) + 0x007f007fu;
+    // bytes 1 and 3 of rnd are the codes: after one shift they sit where the two byte stores read
+    // them (bits 7:0 and 23:16)
+    const uint32_t sh = rnd >> 8;
+    asm volatile("ds_write_b8 %0, %1 offset:%2\n\tds_write_b8_d16_hi %0, %1 offset:%3"
+                 :: "v"(addr), "v"(sh), "n"(128 * T), "n"(128 * T + 4) : "memory");
+    return v - __builtin_bit_cast(half2_t, rnd & 0xff00ff00u);
+}
+
+// max(v, v moved across lanes by DPP control CTRL); rows outside ROWMASK keep v
+template <int CTRL, int ROWMASK = 0xf>
+__device__ __forceinline__ uint32_t max_dpp(uint32_t v)
+{
+    const uint32_t moved = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWMASK, 0xf, false);
+    return max(v, moved);
+}
+
+template <int Q, int G>
+struct MxRegs {
+    static constexpr int GS = G < 128 ? G : 128;
+    static constexpr int SEG = 128 / GS;
+    uint32_t w[Q][4];          // plane j: the four words (32 k each) of column l
+    uint16_t mt[SEG][Q + 1];   // lane <-> column l of the tile
+    uint32_t x;                // activations 2l, 2l+1 of the chunk
+};
+
+// bytes per column of the transposed scale block in LDS (a multiple of 8)
+constexpr int mx_meta_stride(int Q, int G) { return ((128 / (G < 128 ? G : 128)) * (Q + 1) * 2 + 7) & ~7; }
+constexpr int MX_XT_BYTES = 576;     // four terms x 128 bf8, then 16 zero bytes (padded to 64)
+// per wavefront: activation codes | scales [64][stride] | sums [4][64] fp32
+constexpr int mx_wave_lds(int Q, int G) { return MX_XT_BYTES + 64 * mx_meta_stride(Q, G) + 4 * 64 * 4; }
+#ifdef HLQ_MX_NBUF
+constexpr int mx_nbuf(int, int) { return HLQ_MX_NBUF; }
+#else
+constexpr int mx_nbuf(int Q, int G) { return Q * 4 + (128 / (G < 128 ? G : 128)) * (Q + 1) <= 16 ? 4 : 2; }
+#endif
+
+template <int Q, int G>
+__global__ void __launch_bounds__(512)
+hlq_gemv_mx_kernel(const GemvBatch b)
+{
+    using Regs = MxRegs<Q, G>;
+    constexpr int GS = Regs::GS, SEG = Regs::SEG;
+    constexpr int MSTR = mx_meta_stride(Q, G);
+    constexpr int PERW = mx_wave_lds(Q, G);
+    constexpr int NBUF = mx_nbuf(Q, G);
+    const int W = (int)(blockDim.x >> 6);
+    extern __shared__ __attribute__((aligned(256))) char lds[];
+
+    int pi = 0;
+    for (int i = 1; i < b.count; ++i)
+        if ((int)blockIdx.x >= b.p[i].blk_begin) pi = i;
+    const GemvProb &P = b.p[pi];
+    const int local = (int)blockIdx.x - P.blk_begin;
+    const int tile = local / P.nslices, slice = local % P.nslices;
+
+    const int tid = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+    // this wavefront's run of chunks: the slice is cut into W near-equal parts
+    const int sbeg = slice * P.cps;
+    const int send = min(sbeg + P.cps, P.nchunks);
+    const int len = send - sbeg;
+    const int cbeg = sbeg + (len * wave) / W;
+    const int cend = sbeg + (len * (wave + 1)) / W;
+
+    const int tw = hlq_tile_width(tile, P.N);
+    const char *tile_base = P.packed + (size_t)tile * HLQ_TILE_N * P.col_bytes;
+    const int c = lane & 15, g = lane >> 4;
+    // clamped column: loads stay in bounds, results of lanes past the tile's width are dropped
+    const uint32_t moff = (uint32_t)(lane < tw ? lane : tw - 1) * 2u;
+    const uint32_t woff = moff * 8u;   // this lane's 16 bytes inside a plane of a record
+
+    char *xt = lds + wave * PERW;                     // [term][128] bf8 in matrix-core k order, 16 zero bytes
+    char *meta = xt + MX_XT_BYTES;                    // [column][SEG][Q+1] fp16
+    float *red = (float *)(meta + 64 * MSTR);         // [4][64]
+    constexpr int RSTR = PERW / 4;                    // floats between wavefronts' sums
+    if (lane < 4) ((uint32_t *)(xt + 512))[lane] = 0u;
+
+    auto load_chunk = [&](int ch, Regs &R) {
+        const char *rec = tile_base + (size_t)tw * ((size_t)ch * Q * 16 + (size_t)hlq_groups_before(ch, G) * (Q + 1) * 2);
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const uint4 v = *(const uint4 *)(rec + (size_t)(j * tw * 16) + woff);
+            R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
+        }
+        const char *mrec = rec;
+        if (G > 128) {   // the group's scales sit in the record of its first (even) chunk
+            const int c0 = ch & ~1;
+            mrec = tile_base + (size_t)tw * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
+        }
+        const char *m = mrec + (size_t)tw * Q * 16;
+#pragma unroll
+        for (int sg = 0; sg < SEG; ++sg)
+#pragma unroll
+            for (int r = 0; r <= Q; ++r)
+                if (HLQ_MX_DEBUG < 7) R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
+                else R.mt[sg][r] = 0;
+        R.x = *(const uint32_t *)((const char *)(P.x + (size_t)ch * 128) + lane * 4u);
+    };
+
+    // ---- scale: largest magnitude of the run's activations (as fp16 bit patterns) --------------------------
+    // The activation loads go out BEFORE the weight loads: memory returns a wavefront's loads in
+    // order, so the scale is known as soon as x is there, long before the first chunk.
+    const int nrun = cend - cbeg;
+    const uint32_t *xr = (const uint32_t *)(P.x + (size_t)cbeg * 128) + lane;
+    uint32_t xu[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) xu[i] = HLQ_MX_DEBUG >= 6 ? 0u : xr[(size_t)max(min(i, nrun - 1), 0) * 64];
+
+    // weight loads of the first chunks (an empty run re-reads the slice's first chunk and drops it)
+    Regs R[NBUF];
+#pragma unroll
+    for (int i = 0; i < NBUF; ++i) load_chunk(max(min(cbeg + i, cend - 1), sbeg), R[i]);
+
+    uint32_t mx = 0;
+    {
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx),
+                                                                        __builtin_bit_cast(ushort2_t, xu[i] & 0x7fff7fffu)));
+        for (int ci = 8; ci < (HLQ_MX_DEBUG >= 6 ? 0 : nrun); ++ci) {   // runs longer than eight chunks
+            const uint32_t u = xr[(size_t)ci * 64] & 0x7fff7fffu;
+            mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, u)));
+        }
+        mx = max(mx & 0xffffu, mx >> 16);
+        mx = max_dpp<0xB1>(mx);          // quad_perm [1,0,3,2]
+        mx = max_dpp<0x4E>(mx);          // quad_perm [2,3,0,1]
+        mx = max_dpp<0x124>(mx);         // row_ror:4
+        mx = max_dpp<0x128>(mx);         // row_ror:8: every lane holds its row's maximum
+        mx = max_dpp<0x142, 0xa>(mx);    // row_bcast15: rows 1, 3 take rows 0, 2 in
+        mx = max_dpp<0x143, 0xc>(mx);    // row_bcast31: row 3 takes row 1 in
+    }
+    const uint32_t top = HLQ_MX_DEBUG >= 6 ? 0x3c00u : (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
+    // biased fp16 exponent e of the largest magnitude: |x| < 2^(e-14).  Scale by 2^(29-e): |x| < 2^15.
+    // Plane codes are worth 1/2, 1, 2, 2 by register: weights 1/2, 1/4, 1/8, 1/8 make every product
+    // bit x activation / 4.  The factor 2^(29-e) (<= 2^29) is applied as two fp16 multiplications.
+    const int e = (int)(top >> 10);
+    const int r_ = lane & 3;
+    const int k1 = (29 - e) / 2, k2 = (29 - e) - k1 - (r_ == 0 ? 1 : r_ == 1 ? 2 : 3);   // -4 <= k2 <= 14
+    const _Float16 f1 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k1) << 10));
+    const _Float16 f2 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k2) << 10));
+    const half2_t sw1 = {f1, f1}, sw2 = {f2, f2};
+    const float yscale = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + e) << 23);   // 4 * 2^(e-29)
+
+    // ---- activation role: this lane converts x[2l], x[2l+1] of a chunk.  Weight k0 = 2 (l & 15) + h of
+    // block g is plane bit (l & 15) + 16 h, i.e. register r = l & 3, nibble ((l >> 2) & 3) + 4 h of the
+    // expanded word: matrix-core k index 32 g + 8 r + nibble.
+    const uint32_t xt_wa = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)xt +
+                           (uint32_t)(32 * g + 8 * r_ + ((lane >> 2) & 3));
+    // ---- operand role: row (lane & 15) = 4 t + sg of the activation operand, 16-k runs [16 g, 16 g + 16)
+    // and [64 + 16 g, ...) of the chunk; a run outside segment sg reads the zero bytes
+    const int at = (lane & 15) >> 2, asg = lane & 3;
+    const char *a_src[2];
+#pragma unroll
+    for (int hh = 0; hh < 2; ++hh) {
+        const int blk = 2 * hh + (g >> 1);       // 32-k block the run lies in
+        const bool on = asg < SEG && (blk * 32) / GS == asg;
+        a_src[hh] = xt + (on ? 128 * at + 64 * hh + 16 * g : 512);
+    }
+
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
+
+    // Operands that come through LDS, fetched one chunk ahead: the activation operand and, per column
+    // block, the scales of this lane's column (MSTR bytes, fp16).
+    struct Pre {
+        int8v A;
+        uint32_t m[4][MSTR / 4];
+    };
+    auto scale_of = [](const uint32_t (&m)[MSTR / 4], int i) -> float {   // i-th fp16 of a scale record
+        const half2_t h = __builtin_bit_cast(half2_t, m[i >> 1]);
+        return (float)((i & 1) ? h.y : h.x);
+    };
+    auto prefetch = [&](const Regs &Rn, Pre &pn) {
+        // activations -> four bf8 terms (bytes = high bytes of fp16 values with three significant bits)
+        {
+            half2_t v = (__builtin_bit_cast(half2_t, Rn.x) * sw1) * sw2;   // exact: powers of two, in range
+            v = put_term<0>(xt_wa, v);
+            v = put_term<1>(xt_wa, v);
+            v = put_term<2>(xt_wa, v);
+            (void)put_term<3>(xt_wa, v);
+        }
+        // scales: lane <-> column to LDS, read back per column block
+#pragma unroll
+        for (int sg = 0; sg < SEG; ++sg)
+#pragma unroll
+            for (int r = 0; r <= Q; ++r) ((uint16_t *)(meta + lane * MSTR))[sg * (Q + 1) + r] = Rn.mt[sg][r];
+        const uint4 alo = *(const uint4 *)a_src[0];
+        const uint4 ahi = *(const uint4 *)a_src[1];
+        pn.A = (int8v){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, (int)ahi.z, (int)ahi.w};
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int i = 0; i < MSTR / 4; ++i) pn.m[cb][i] = ((const uint32_t *)(meta + (16 * cb + c) * MSTR))[i];
+    };
+    auto expand = [](uint32_t w) -> int8v {   // plane word -> 32 fp4 codes (bit 4p+r -> nibble p of register r)
+        return (int8v){(int)(w & 0x11111111u), (int)(w & 0x22222222u), (int)(w & 0x44444444u),
+                       (int)((w >> 1) & 0x44444444u), 0, 0, 0, 0};
+    };
+
+    // One chunk.  The matrix core takes ~32 cycles per MFMA and the wavefront issues in order, so the
+    // step is written as a software pipeline: each stage issues the MFMA of item n (plane j of column
+    // block cb), expands the plane word of item n+1 and applies the scales to the result of item
+    // n-1; scheduling barriers keep the stages apart.  The LDS operands of the NEXT chunk are fetched
+    // in the middle of the step.
+    auto step = [&](const Regs &R, const Pre &p, const Regs &Rn, Pre &pn) {
+        if (HLQ_MX_DEBUG == 1 || HLQ_MX_DEBUG >= 3) {   // timing experiment: loads only
+            uint32_t m = 0;
+#pragma unroll
+            for (int j = 0; j < Q; ++j) m ^= R.w[j][0] ^ R.w[j][1] ^ R.w[j][2] ^ R.w[j][3];
+#pragma unroll
+            for (int r = 0; r <= Q; ++r) m ^= R.mt[0][r];
+            acc[0] += (float)m;
+            return;
+        }
+        constexpr int NI = 4 * Q;   // items; item n: column block n / Q, plane n % Q
+        // segment sums of x for the zero points: all-ones plane
+        const int8v ones = {0x11111111, 0x22222222, 0x44444444, 0x44444444, 0, 0, 0, 0};
+        const float4v xs = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A, ones, zero4, 1, 4, 0, 0, 0, 0);
+        // 4 x 4 transpose over (16-lane group, word): afterwards wt[j][cb] of lane (c, g) is word g of
+        // column 16 cb + c
+        uint32_t wt[Q][4];
+#pragma unroll
+        for (int j = 0; j < Q; ++j) {
+            const uint2v s01 = __builtin_amdgcn_permlane16_swap(R.w[j][0], R.w[j][1], false, false);
+            const uint2v s23 = __builtin_amdgcn_permlane16_swap(R.w[j][2], R.w[j][3], false, false);
+            const uint2v t02 = __builtin_amdgcn_permlane32_swap(s01.x, s23.x, false, false);
+            const uint2v t13 = __builtin_amdgcn_permlane32_swap(s01.y, s23.y, false, false);
+            wt[j][0] = t02.x; wt[j][2] = t02.y; wt[j][1] = t13.x; wt[j][3] = t13.y;
+        }
+        int8v B = expand(wt[0][0]);
+        float4v d[3];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int n = 0; n < NI; ++n) {
+            d[n % 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A, B, zero4, 1, 4, 0, 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (n + 1 < NI) B = expand(wt[(n + 1) % Q][(n + 1) / Q]);
+            if (n >= 1) {
+                const int cb = (n - 1) / Q, j = (n - 1) % Q;
+#pragma unroll
+                for (int sg = 0; sg < SEG; ++sg) acc[cb] += scale_of(p.m[cb], sg * (Q + 1) + j) * d[(n - 1) % 3][sg];
+                // keeps all four result registers allocated up to here: if the unused ones were handed
+                // to the next operand while the MFMA is in flight, every write to them would have to
+                // wait for it
+                asm volatile("" ::"v"(d[(n - 1) % 3]));
+            }
+            if (n == 1) prefetch(Rn, pn);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        {
+            const int cb = (NI - 1) / Q, j = (NI - 1) % Q;
+#pragma unroll
+            for (int sg = 0; sg < SEG; ++sg) acc[cb] += scale_of(p.m[cb], sg * (Q + 1) + j) * d[(NI - 1) % 3][sg];
+        }
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int sg = 0; sg < SEG; ++sg) acc[cb] += scale_of(p.m[cb], sg * (Q + 1) + Q) * xs[sg];
+    };
+
+    // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
+    Pre pre[2];
+    if (cbeg < cend && !(HLQ_MX_DEBUG == 1 || HLQ_MX_DEBUG >= 3)) prefetch(R[0], pre[0]);
+    for (int ch = cbeg; ch < cend; ch += NBUF) {
+#pragma unroll
+        for (int i = 0; i < NBUF; ++i) {
+            if (ch + i < cend) step(R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1]);
+            if (HLQ_MX_DEBUG != 2) load_chunk(max(min(ch + i + NBUF, cend - 1), sbeg), R[i]);
+        }
+    }
+
+    // ---- undo the run's scaling; add the four terms (lane groups) and the W runs -----------------------------
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) red[cb * 64 + lane] = acc[cb] * yscale;
+    if (HLQ_MX_DEBUG != 8) __syncthreads();
+    if (wave != 0) return;
+    float y = 0.f;
+    for (int w2 = 0; w2 < W; ++w2)
+#pragma unroll
+        for (int g2 = 0; g2 < 4; ++g2) y += red[w2 * RSTR + (lane >> 4) * 64 + (lane & 15) + 16 * g2];
+    const bool col_ok = lane < tw;
+    const size_t n = (size_t)tile * HLQ_TILE_N + lane;
+
+    if (P.nslices == 1 || HLQ_MX_DEBUG == 5) {
+        if (col_ok) store_out(P.y, n, y, b.out_f32);
+        return;
+    }
+    // ---- split-K across workgroups: write-through partials, arrival counter, last one adds in slice order
+    if (col_ok) __hip_atomic_store(&P.part[(size_t)slice * P.N + n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    int old = 0;
+    if (lane == 0) old = __hip_atomic_fetch_add(&P.cnt[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if (old != P.nslices - 1) return;
+    if (col_ok) {
+        float a = 0.f;
+        int sl = 0;
+        for (; sl + 4 <= P.nslices; sl += 4) {
+            const float v0 = __hip_atomic_load(&P.part[(size_t)(sl + 0) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float v1 = __hip_atomic_load(&P.part[(size_t)(sl + 1) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float v2 = __hip_atomic_load(&P.part[(size_t)(sl + 2) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const float v3 = __hip_atomic_load(&P.part[(size_t)(sl + 3) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            a = (((a + v0) + v1) + v2) + v3;
+        }
+        for (; sl < P.nslices; ++sl)
+            a += __hip_atomic_load(&P.part[(size_t)sl * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        store_out(P.y, n, a, b.out_f32);
+    }
+    if (lane == 0) __hip_atomic_store(&P.cnt[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int Q, int G>
+void launch_qg(const GemvBatch &b, unsigned nblocks, int W, hipStream_t st)
+{
+    hlq_gemv_mx_kernel<Q, G><<<nblocks, dim3(64 * W), (size_t)W * mx_wave_lds(Q, G), st>>>(b);
+}
+
+template <int Q>
+hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, hipStream_t st)
+{
+    switch (G) {
+    case 32: launch_qg<Q, 32>(b, nblocks, W, st); return HLQ_OK;
+    case 64: launch_qg<Q, 64>(b, nblocks, W, st); return HLQ_OK;
+    case 128: launch_qg<Q, 128>(b, nblocks, W, st); return HLQ_OK;
+    case 256: launch_qg<Q, 256>(b, nblocks, W, st); return HLQ_OK;
+    }
+    return HLQ_ERR_UNSUPPORTED;
+}
+
+} // namespace
+
+int hlq_gemv_mx_max_waves(int, int) { return 8; }
+
+hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st)
+{
+    if (W < 1 || W > 8) return HLQ_ERR_UNSUPPORTED;
+    switch (q) {
+    case 1: return launch_q<1>(G, b, nblocks, W, st);
+    case 2: return launch_q<2>(G, b, nblocks, W, st);
+    case 3: return launch_q<3>(G, b, nblocks, W, st);
+    case 4: return launch_q<4>(G, b, nblocks, W, st);
+    }
+    return HLQ_ERR_UNSUPPORTED;
+}

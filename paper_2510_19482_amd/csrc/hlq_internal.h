@@ -96,6 +96,7 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
                            hipStream_t st);
 hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st);
 hlq_status hlq_gemv_plan_override(int tn, int w, int cpw);
+hlq_status hlq_gemv_path_override(int path);
 
 // Workspace = [HLQ_WS_COUNTER_BYTES of split-K arrival counters][fp32 partial sums].
 // Counters are zero between calls (hlq_workspace_init zeroes them; kernels re-zero them).

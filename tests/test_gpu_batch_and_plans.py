@@ -26,7 +26,7 @@ def auto_plan():
 @pytest.mark.parametrize("tn,w,cpw", [(1, 1, 1), (1, 2, 3), (1, 4, 1), (1, 8, 2), (1, 16, 1), (2, 4, 2),
                                       (2, 8, 1), (2, 16, 3), (2, 1, 64), (1, 4, 64)])
 @pytest.mark.parametrize("q,G", [(2, 128), (3, 128), (1, 64), (2, 256), (4, 32)])
-def test_gemv_every_launch_shape(tn, w, cpw, q, G):
+def test_gemv_every_launch_shape(tn, w, cpw, q, G, gemv_path):
     K, N = 2304, 1096            # 18 chunks, 17 full tiles + a 8-column tail
     say("plan", tn, w, cpw, "q", q, "G", G)
     B.set_gemv_plan(tn, w, cpw)
@@ -35,7 +35,7 @@ def test_gemv_every_launch_shape(tn, w, cpw, q, G):
     d, packed = pack_on_gpu(codes, S, Z, q, G)
     ref = O.gemm_dequant(x, codes, S, Z, q, G)
     y = gemv_gpu(d, packed, x[0], out_f32=True)
-    assert O.row_rel_err(y, ref).max() <= 2e-5
+    assert O.row_rel_err(y, ref).max() <= gemv_path
     y2 = gemv_gpu(d, packed, x[0], out_f32=True)
     assert np.array_equal(y, y2)          # split-K order is fixed
 
@@ -47,7 +47,7 @@ def test_bad_plan_rejected():
 
 
 @pytest.mark.parametrize("q", [2, 3])
-def test_batch_equals_single_calls_and_oracle(q):
+def test_batch_equals_single_calls_and_oracle(q, gemv_path):
     G = 128
     shapes = [synth.Shape("a", 1024, 520), synth.Shape("b", 512, 64), synth.Shape("c", 2048, 1032),
               synth.Shape("d", 1024, 8)]
@@ -65,7 +65,7 @@ def test_batch_equals_single_calls_and_oracle(q):
         torch.cuda.synchronize()
         for s, y, ref in zip(shapes, ys, refs):
             got = y.cpu().numpy().astype(np.float64)[None, :]
-            assert O.row_rel_err(got, ref).max() <= 2e-5, s.name
+            assert O.row_rel_err(got, ref).max() <= gemv_path, s.name
 
 
 def test_batch_argument_errors():
@@ -93,4 +93,4 @@ def test_one_workspace_serves_different_shapes():
         y = B.hlq_lut_gemv(d, packed, dev(x[0]), out_f32=True, ws=ws)
         torch.cuda.synchronize()
         ref = c_oracle.gemm_f64(x, codes, S, Z, q, G)
-        assert O.row_rel_err(y.cpu().numpy().astype(np.float64)[None, :], ref).max() <= 2e-5
+        assert O.row_rel_err(y.cpu().numpy().astype(np.float64)[None, :], ref).max() <= 2e-4   # default path
