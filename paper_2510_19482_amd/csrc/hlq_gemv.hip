@@ -456,8 +456,8 @@ GemvPlan plan_gemv(long units)
     if (use_mx()) {
         // matrix-core kernel (sweeps on the same shapes): short runs on many wavefronts while the
         // launch is small, longer runs once the chip is full
-        pl.W = units < 12000 ? 8 : units < 65536 ? 4 : 8;
-        pl.cpw = units < 12000 ? 4 : 8;
+        pl.W = 8;
+        pl.cpw = units < 12000 ? 4 : 7;
     }
     if (env_tn) pl.TN = env_tn;
     if (env_w) pl.W = env_w;
@@ -520,6 +520,8 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         if (mx || !gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
         const int maxw = mx ? hlq_gemv_mx_max_waves(q0, G0) : gemv_max_threads(q0, G0, pl.TN) / 64;
         if (pl.W > maxw) pl.W = maxw;
+        if (mx)   // a power of two
+            while (pl.W & (pl.W - 1)) pl.W &= pl.W - 1;
     }
     if (pl.W < 1 || pl.W > 16 || (pl.TN != 1 && pl.TN != 2) || pl.cpw < 1) return HLQ_ERR_UNSUPPORTED;
     // chunks per K slice of the lookup kernel: each of its W wavefronts takes cpw chunks of one tile
@@ -533,12 +535,12 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     float *part = (float *)((char *)ws + HLQ_WS_COUNTER_BYTES);
     long blk = 0;
     long cnt_used = 0;
-    // Workgroups start in block order: problems whose K is split across workgroups go first, so the
-    // extra trips to memory at their end overlap with the other problems' streaming.
+    // Workgroups start in block order: problems with long K (long runs, or K split across workgroups
+    // with extra trips to memory at the end) go first.
     int order[HLQ_MAX_BATCH];
     for (int i = 0; i < count; ++i) order[i] = i;
     for (int i = 1; i < count; ++i)
-        for (int j = i; j > 0 && slices_for(items[order[j]].dm, cps) > slices_for(items[order[j - 1]].dm, cps); --j) {
+        for (int j = i; j > 0 && items[order[j]].dm.nchunks > items[order[j - 1]].dm.nchunks; --j) {
             const int t = order[j];
             order[j] = order[j - 1];
             order[j - 1] = t;
@@ -553,15 +555,30 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         p.N = dm.N;
         p.nchunks = dm.nchunks;
         p.ntiles = dm.ntiles;
-        p.ntg = (dm.ntiles + pl.TN - 1) / pl.TN;
-        p.nslices = slices_for(dm, cps);
+        p.kw = 1;
+        if (mx) {
+            const int cpw_i = pl.cpw;
+            // Runs of about cpw chunks for every problem of the launch (wavefronts with longer runs would
+            // finish alone, with the memory system half idle): cut K inside the workgroup first (kw
+            // wavefronts per tile), then across workgroups.
+            while (p.kw * 2 <= pl.W && dm.nchunks / (p.kw * 2) >= cpw_i) p.kw *= 2;
+            int per_slice = p.kw * cpw_i;
+            if (per_slice < 4) per_slice = 4;
+            p.nslices = (dm.nchunks + per_slice / 2) / per_slice;   // nearest
+            if (p.nslices < 1) p.nslices = 1;
+            const int tiles_per_wg = pl.W / p.kw;
+            p.ntg = (dm.ntiles + tiles_per_wg - 1) / tiles_per_wg;
+        } else {
+            p.ntg = (dm.ntiles + pl.TN - 1) / pl.TN;
+            p.nslices = slices_for(dm, cps);
+        }
         p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
         p.blk_begin = (int)blk;
         p.cnt = cnt + cnt_used;
         p.part = part;
         blk += (long)p.ntg * p.nslices;
         if (p.nslices > 1) {
-            cnt_used += p.ntg;
+            cnt_used += mx ? dm.ntiles : p.ntg;
             part += (size_t)p.nslices * dm.N;
         }
     }

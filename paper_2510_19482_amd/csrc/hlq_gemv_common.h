@@ -14,6 +14,7 @@ struct GemvProb {
     int *cnt;          // [ntg] arrival counters, zero between launches
     size_t col_bytes;
     int N, nchunks, ntiles, ntg, nslices, cps, blk_begin;
+    int kw;            // matrix-core kernel: wavefronts per tile (runs a slice is cut into)
 };
 
 struct GemvBatch {
@@ -30,7 +31,7 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
     else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
 }
 
-// matrix-core formulation (hlq_gemv_mx.hip): same work split as the lookup kernel with one tile per
-// wavefront (ntg = ntiles)
+// matrix-core formulation (hlq_gemv_mx.hip): W (a power of two) wavefronts per workgroup, kw of them
+// per tile: ntg = ceil(ntiles / (W / kw)) tile groups, one arrival counter per TILE
 hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st);
 int hlq_gemv_mx_max_waves(int q, int G);

@@ -10,7 +10,7 @@
 //                the word lands in nibble p of register r as the code 1, 2, 4 or 4 (value 0.5, 1,
 //                2, 2).  No table, no LDS traffic, 5 VALU operations per 32 weights.
 //   activations  x (fp16) is written as an exact sum of four bf8 (e5m2) terms, x = t0+t1+t2+t3
-//                (each term is the running remainder rounded to three significant bits, so after
+//                (each term is the running remainder cut to three significant bits, so after
 //                four terms all eleven bits of an fp16 significand are covered), after a power-of-
 //                two weight (1/2, 1/4, 1/8, 1/8 by register r) that evens out the plane codes.  The
 //                four terms occupy four ROWS of the 16-row operand; with quant groups shorter than
@@ -24,11 +24,14 @@
 // bits, so a product loses bits only if it is more than 2^10 times smaller than its largest
 // neighbour, and then less than 2^-13 of that neighbour.  Everything else is exact fp32 work.
 //
-// Work split (that of the lookup kernel, hlq_gemv.hip).  A workgroup owns one column tile and one K
-// slice; its W wavefronts take W consecutive runs of chunks of the slice and add their results
-// through LDS; slices of different workgroups meet in the workspace (partial sums, one arrival
-// counter per tile, the last workgroup adds in slice order).  Everything up to the final sum is
-// private to the wavefront, so the chunk loop has no barrier:
+// Work split.  A workgroup of W wavefronts owns W / kw adjacent column tiles and one K slice; the kw
+// wavefronts of a tile take kw consecutive runs of chunks of the slice and add their results through
+// LDS (kw is chosen per problem, so that short and long K in one grouped launch get runs of similar
+// length).  Slices of different workgroups meet in the workspace as in the lookup kernel
+// (hlq_gemv.hip: partial sums, one arrival counter per tile, the last workgroup adds in slice
+// order); that costs three dependent trips to device memory at the end of a workgroup, so the host
+// splits K inside the workgroup first.  Everything up to the final sum is private to the wavefront,
+// so the chunk loop has no barrier:
 //
 //   scale     the largest |x| of the wavefront's run fixes a power-of-two scale that puts the
 //             activations high in the bf8 range; it is removed from the result at the end, so
@@ -56,20 +59,19 @@ typedef int int8v __attribute__((ext_vector_type(8)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
 
-// Rounds the pair v to three significant bits (nearest, ties to even), stores the two bf8 codes at
-// LDS bytes addr + 128 T and addr + 128 T + 4, returns the remainder (exact).  |v| < 61440, so the
-// rounding cannot reach infinity.
+// Cuts the pair v to three significant bits (the high byte of each fp16 is a bf8 code: sign, exponent,
+// two mantissa bits), stores the two codes at LDS bytes addr + 128 T and addr + 128 T + 4, returns
+// the remainder (exact).  Each term strips at least three leading bits of the significand, so four
+// terms hold all eleven bits of an fp16 value.
 template <int T>
 __device__ __forceinline__ half2_t put_term(uint32_t addr, half2_t v)
 {
     const uint32_t u = __builtin_bit_cast(uint32_t, v);
-    const uint32_t rnd = u + ((u >> 8) & 0x00010001u) + 0x007f007fu;
-    // bytes 1 and 3 of rnd are the codes: after one shift they sit where the two byte stores read
-    // them (bits 7:0 and 23:16)
-    const uint32_t sh = rnd >> 8;
+    // after one shift the codes sit where the two byte stores read them (bits 7:0 and 23:16)
+    const uint32_t sh = u >> 8;
     asm volatile("ds_write_b8 %0, %1 offset:%2\n\tds_write_b8_d16_hi %0, %1 offset:%3"
                  :: "v"(addr), "v"(sh), "n"(128 * T), "n"(128 * T + 4) : "memory");
-    return v - __builtin_bit_cast(half2_t, rnd & 0xff00ff00u);
+    return v - __builtin_bit_cast(half2_t, u & 0xff00ff00u);
 }
 
 // max(v, v moved across lanes by DPP control CTRL); rows outside ROWMASK keep v
@@ -94,10 +96,13 @@ constexpr int mx_meta_stride(int Q, int G) { return ((128 / (G < 128 ? G : 128))
 constexpr int MX_XT_BYTES = 576;     // four terms x 128 bf8, then 16 zero bytes (padded to 64)
 // per wavefront: activation codes | scales [64][stride] | sums [4][64] fp32
 constexpr int mx_wave_lds(int Q, int G) { return MX_XT_BYTES + 64 * mx_meta_stride(Q, G) + 4 * 64 * 4; }
+// Register sets of chunk loads per wavefront (chunks in flight + 1).  Two: launches of this kernel
+// have thousands of wavefronts, which together keep far more than the bandwidth-delay product in
+// flight; deeper prefetch only costs registers, i.e. resident wavefronts (measured: 2 beats 3, 4, 6, 8).
 #ifdef HLQ_MX_NBUF
 constexpr int mx_nbuf(int, int) { return HLQ_MX_NBUF; }
 #else
-constexpr int mx_nbuf(int Q, int G) { return Q * 4 + (128 / (G < 128 ? G : 128)) * (Q + 1) <= 16 ? 4 : 2; }
+constexpr int mx_nbuf(int, int) { return 2; }
 #endif
 
 template <int Q, int G>
@@ -112,28 +117,40 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     const int W = (int)(blockDim.x >> 6);
     extern __shared__ __attribute__((aligned(256))) char lds[];
 
+#if HLQ_MX_DEBUG == 9
+    long long ts[8];
+    ts[0] = wall_clock64();
+#define HLQ_TS(i) ts[i] = wall_clock64()
+#else
+#define HLQ_TS(i)
+#endif
     int pi = 0;
     for (int i = 1; i < b.count; ++i)
         if ((int)blockIdx.x >= b.p[i].blk_begin) pi = i;
     const GemvProb &P = b.p[pi];
     const int local = (int)blockIdx.x - P.blk_begin;
-    const int tile = local / P.nslices, slice = local % P.nslices;
+    const int tg = local / P.nslices, slice = local % P.nslices;
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    // this wavefront's run of chunks: the slice is cut into W near-equal parts
+    const int KW = P.kw, part = wave % KW;
+    const int tile = tg * (W / KW) + wave / KW;
+    const bool tile_ok = tile < P.ntiles;               // a surplus wavefront gets an empty run
+    const int tile_c = tile_ok ? tile : P.ntiles - 1;
+    // this wavefront's run of chunks: the slice is cut into KW near-equal parts
     const int sbeg = slice * P.cps;
     const int send = min(sbeg + P.cps, P.nchunks);
     const int len = send - sbeg;
-    const int cbeg = sbeg + (len * wave) / W;
-    const int cend = sbeg + (len * (wave + 1)) / W;
+    const int cbeg = sbeg + (len * part) / KW;
+    const int cend = tile_ok ? sbeg + (len * (part + 1)) / KW : cbeg;
 
-    const int tw = hlq_tile_width(tile, P.N);
-    const char *tile_base = P.packed + (size_t)tile * HLQ_TILE_N * P.col_bytes;
+    const int tw = hlq_tile_width(tile_c, P.N);
+    const char *tile_base = P.packed + (size_t)tile_c * HLQ_TILE_N * P.col_bytes;
     const int c = lane & 15, g = lane >> 4;
     // clamped column: loads stay in bounds, results of lanes past the tile's width are dropped
-    const uint32_t moff = (uint32_t)(lane < tw ? lane : tw - 1) * 2u;
-    const uint32_t woff = moff * 8u;   // this lane's 16 bytes inside a plane of a record
+    uint32_t moff = (uint32_t)(lane < tw ? lane : tw - 1) * 2u;
+    uint32_t woff = moff * 8u;   // this lane's 16 bytes inside a plane of a record
+    uint32_t xoff = (uint32_t)lane * 4u;
 
     char *xt = lds + wave * PERW;                     // [term][128] bf8 in matrix-core k order, 16 zero bytes
     char *meta = xt + MX_XT_BYTES;                    // [column][SEG][Q+1] fp16
@@ -142,6 +159,10 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     if (lane < 4) ((uint32_t *)(xt + 512))[lane] = 0u;
 
     auto load_chunk = [&](int ch, Regs &R) {
+        // The lane offsets pass through an empty asm: they are re-extended to 64 bits at each use,
+        // which lets the loads take the form "scalar base + 32-bit lane offset" instead of one 64-bit
+        // vector add each.
+        asm volatile("" : "+v"(woff), "+v"(moff), "+v"(xoff));
         const char *rec = tile_base + (size_t)tw * ((size_t)ch * Q * 16 + (size_t)hlq_groups_before(ch, G) * (Q + 1) * 2);
 #pragma unroll
         for (int j = 0; j < Q; ++j) {
@@ -158,9 +179,9 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         for (int sg = 0; sg < SEG; ++sg)
 #pragma unroll
             for (int r = 0; r <= Q; ++r)
-                if (HLQ_MX_DEBUG < 7) R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
+                if (HLQ_MX_DEBUG < 7 || HLQ_MX_DEBUG > 8) R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
                 else R.mt[sg][r] = 0;
-        R.x = *(const uint32_t *)((const char *)(P.x + (size_t)ch * 128) + lane * 4u);
+        R.x = *(const uint32_t *)((const char *)(P.x + (size_t)ch * 128) + xoff);
     };
 
     // ---- scale: largest magnitude of the run's activations (as fp16 bit patterns) --------------------------
@@ -170,7 +191,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     const uint32_t *xr = (const uint32_t *)(P.x + (size_t)cbeg * 128) + lane;
     uint32_t xu[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xu[i] = HLQ_MX_DEBUG >= 6 ? 0u : xr[(size_t)max(min(i, nrun - 1), 0) * 64];
+    for (int i = 0; i < 8; ++i) xu[i] = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0u : xr[(size_t)max(min(i, nrun - 1), 0) * 64];
 
     // weight loads of the first chunks (an empty run re-reads the slice's first chunk and drops it)
     Regs R[NBUF];
@@ -183,7 +204,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         for (int i = 0; i < 8; ++i)
             mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx),
                                                                         __builtin_bit_cast(ushort2_t, xu[i] & 0x7fff7fffu)));
-        for (int ci = 8; ci < (HLQ_MX_DEBUG >= 6 ? 0 : nrun); ++ci) {   // runs longer than eight chunks
+        for (int ci = 8; ci < ((HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0 : nrun); ++ci) {   // runs longer than eight chunks
             const uint32_t u = xr[(size_t)ci * 64] & 0x7fff7fffu;
             mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, u)));
         }
@@ -195,7 +216,8 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         mx = max_dpp<0x142, 0xa>(mx);    // row_bcast15: rows 1, 3 take rows 0, 2 in
         mx = max_dpp<0x143, 0xc>(mx);    // row_bcast31: row 3 takes row 1 in
     }
-    const uint32_t top = HLQ_MX_DEBUG >= 6 ? 0x3c00u : (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
+    HLQ_TS(1);
+    const uint32_t top = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0x3c00u : (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
     // biased fp16 exponent e of the largest magnitude: |x| < 2^(e-14).  Scale by 2^(29-e): |x| < 2^15.
     // Plane codes are worth 1/2, 1, 2, 2 by register: weights 1/2, 1/4, 1/8, 1/8 make every product
     // bit x activation / 4.  The factor 2^(29-e) (<= 2^29) is applied as two fp16 multiplications.
@@ -268,14 +290,15 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     // block cb), expands the plane word of item n+1 and applies the scales to the result of item
     // n-1; scheduling barriers keep the stages apart.  The LDS operands of the NEXT chunk are fetched
     // in the middle of the step.
-    auto step = [&](const Regs &R, const Pre &p, const Regs &Rn, Pre &pn) {
-        if (HLQ_MX_DEBUG == 1 || HLQ_MX_DEBUG >= 3) {   // timing experiment: loads only
+    auto step = [&](Regs &R, const Pre &p, const Regs &Rn, Pre &pn, int ch_reload) {
+        if (HLQ_MX_DEBUG == 1 || (HLQ_MX_DEBUG >= 3 && HLQ_MX_DEBUG <= 8)) {   // timing experiment: loads only
             uint32_t m = 0;
 #pragma unroll
             for (int j = 0; j < Q; ++j) m ^= R.w[j][0] ^ R.w[j][1] ^ R.w[j][2] ^ R.w[j][3];
 #pragma unroll
             for (int r = 0; r <= Q; ++r) m ^= R.mt[0][r];
             acc[0] += (float)m;
+            load_chunk(ch_reload, R);
             return;
         }
         constexpr int NI = 4 * Q;   // items; item n: column block n / Q, plane n % Q
@@ -293,6 +316,9 @@ hlq_gemv_mx_kernel(const GemvBatch b)
             const uint2v t13 = __builtin_amdgcn_permlane32_swap(s01.y, s23.y, false, false);
             wt[j][0] = t02.x; wt[j][2] = t02.y; wt[j][1] = t13.x; wt[j][3] = t13.y;
         }
+        // this register set is free from here on (its scales and activations were consumed one chunk
+        // ahead): refill it now, before the MFMAs, so the next request is not held up by them
+        if (HLQ_MX_DEBUG != 2) load_chunk(ch_reload, R);
         int8v B = expand(wt[0][0]);
         float4v d[3];
         __builtin_amdgcn_sched_barrier(0);
@@ -325,23 +351,34 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     };
 
     // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
+    HLQ_TS(2);
     Pre pre[2];
-    if (cbeg < cend && !(HLQ_MX_DEBUG == 1 || HLQ_MX_DEBUG >= 3)) prefetch(R[0], pre[0]);
+    if (cbeg < cend && !(HLQ_MX_DEBUG == 1 || (HLQ_MX_DEBUG >= 3 && HLQ_MX_DEBUG <= 8))) prefetch(R[0], pre[0]);
     for (int ch = cbeg; ch < cend; ch += NBUF) {
 #pragma unroll
         for (int i = 0; i < NBUF; ++i) {
-            if (ch + i < cend) step(R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1]);
-            if (HLQ_MX_DEBUG != 2) load_chunk(max(min(ch + i + NBUF, cend - 1), sbeg), R[i]);
+            if (ch + i < cend) step(R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1], min(ch + i + NBUF, cend - 1));
         }
     }
 
-    // ---- undo the run's scaling; add the four terms (lane groups) and the W runs -----------------------------
+    HLQ_TS(3);
+    // ---- undo the run's scaling; add the four terms (lane groups) and the tile's KW runs ---------------------
 #pragma unroll
     for (int cb = 0; cb < 4; ++cb) red[cb * 64 + lane] = acc[cb] * yscale;
     if (HLQ_MX_DEBUG != 8) __syncthreads();
-    if (wave != 0) return;
+    HLQ_TS(4);
+#if HLQ_MX_DEBUG == 9
+    if (lane == 0 && wave == 0) {
+        ts[5] = (long long)acc[0];
+        long long *dst = (long long *)((char *)b.p[0].cnt + 65536) + (size_t)(blockIdx.x % 1000) * 8;
+        for (int i = 0; i < 6; ++i) dst[i] = ts[i];
+        dst[6] = pi;
+        dst[7] = cend - cbeg;
+    }
+#endif
+    if (part != 0 || !tile_ok) return;
     float y = 0.f;
-    for (int w2 = 0; w2 < W; ++w2)
+    for (int w2 = 0; w2 < KW; ++w2)
 #pragma unroll
         for (int g2 = 0; g2 < 4; ++g2) y += red[w2 * RSTR + (lane >> 4) * 64 + (lane & 15) + 16 * g2];
     const bool col_ok = lane < tw;
@@ -399,7 +436,7 @@ int hlq_gemv_mx_max_waves(int, int) { return 8; }
 
 hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st)
 {
-    if (W < 1 || W > 8) return HLQ_ERR_UNSUPPORTED;
+    if (W < 1 || W > 8 || (W & (W - 1))) return HLQ_ERR_UNSUPPORTED;
     switch (q) {
     case 1: return launch_q<1>(G, b, nblocks, W, st);
     case 2: return launch_q<2>(G, b, nblocks, W, st);
