@@ -98,8 +98,11 @@ HLQ_API hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint1
 HLQ_API hlq_status hlq_unpack(const hlq_desc *d, const void *packed, uint8_t *codes,
                       uint16_t *scales, uint16_t *zeros, void *stream);
 
-/* y[N] = x[K] @ W^  (M = 1 decode; Sec. 2 / App. B procedure).
- *   x fp16 [K]; y fp16 or fp32 [N] per `out`, overwritten (beta = 0), fp16 by
+/* y[N] = x[K] @ W^  (M = 1 decode; Sec. 2, Eq. 5-6: per plane and quant group the dot product
+ * <b_j, x>, times s_j, plus z times the group's activation sum).  The per-plane dot products are
+ * taken either on the matrix cores (default) or with the 16-entry tables of App. B, see
+ * hlq_set_gemv_path; W^ is never formed.
+ *   x fp16 [K], finite; y fp16 or fp32 [N] per `out`, overwritten (beta = 0), fp16 by
  *   round-to-nearest-even from the fp32 accumulator.
  *   ws / ws_bytes: workspace of at least hlq_workspace_bytes(d, 1). */
 HLQ_API hlq_status hlq_lut_gemv(const hlq_desc *d, const void *packed, const uint16_t *x, void *y,

@@ -129,39 +129,70 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
 
     const _Float16 *xrow = Xs + (size_t)(lane & 31) * XROW + (lane >> 5) * 8;   // this lane's A-fragment origin
 
+    // One chunk = 8 MW steps; step s = ((word d, k-step ks), row block mb) issues the two MFMAs of row
+    // block mb against the two 32-column halves of the tile.  The wavefront issues in order and an
+    // MFMA takes 64 cycles, so everything else is spread between the MFMAs as side work of a step,
+    // one stage ahead of its use (scheduling barriers keep the stages apart):
+    //   - the A fragment of step s + 1 (one 128-bit LDS read) is requested before the MFMAs of step s;
+    //   - the 16 weight pairs of word d + 1 are rebuilt 16 / (2 MW) per step during word d;
+    //   - the four lane exchanges that form the B operands of the next k-step are spread over the MW
+    //     steps of the current one.
     auto compute = [&](const Regs &R, int buf) {
         const _Float16 *xb = xrow + (size_t)buf * ROWS * XROW;
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-            constexpr int dummy = 0;
-            (void)dummy;
-            const int sg = (d * 32) / GS;
-            HlqSegScales<Q> sc;
-            sc.set(R.mt[sg]);
-            uint32_t wd[Q];
+        constexpr int STEPS = 8 * MW, SPW = 2 * MW, PPS = 16 / SPW, XPS = (4 + MW - 1) / MW;
+        auto frag = [&](int s) -> half8v {
+            const int mb = s % MW, ks = (s / MW) & 1, d = s / SPW;
+            return *(const half8v *)(xb + (size_t)mb * 32 * XROW + d * 32 + ks * 16);
+        };
+        uint32_t wp[2][16];   // rebuilt pairs of the current / next word: wp[d & 1][p] = k 32d + 2p, 2p + 1
+        HlqSegScales<Q> sc;
+        uint32_t wd[Q];
+        auto word_setup = [&](int d) {
+            sc.set(R.mt[(d * 32) / GS]);
 #pragma unroll
             for (int j = 0; j < Q; ++j) wd[j] = R.w[j][d];
-            uint32_t wp[16];   // rebuilt weights, register pi = (k = 32d + 2*pi, k = 32d + 2*pi + 1)
-            hlq_rebuild_word<Q>(wd, sc, wp);
+        };
+        // B operands of a k-step: after the exchange lo = columns 0..31 of the tile (lanes 0..31 hold
+        // k-slots 0..7, lanes 32..63 slots 8..15), hi = columns 32..63
+        uint4v lo_c, hi_c, lo_n, hi_n;
+        auto exchange = [&](int d, int ks, int v, uint4v &lo, uint4v &hi) {
+            const uint2v r = __builtin_amdgcn_permlane32_swap(wp[d & 1][ks * 8 + v], wp[d & 1][ks * 8 + 4 + v], false, false);
+            lo[v] = r.x;
+            hi[v] = r.y;
+        };
+        // prologue: word 0 in full, operands of its first k-step, first fragment
+        word_setup(0);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {   // two k-steps of 16 per 32-k block
-                // after the exchange: lo = B operand of columns 0..31 of the tile (lanes 0..31 hold
-                // k-slots 0..7, lanes 32..63 slots 8..15), hi = B operand of columns 32..63
-                uint4v lo, hi;
+        for (int p = 0; p < 16; ++p) wp[0][p] = hlq_rebuild_pair<Q>(wd, sc, p);
 #pragma unroll
-                for (int v = 0; v < 4; ++v) {
-                    const uint2v r = __builtin_amdgcn_permlane32_swap(wp[ks * 8 + v], wp[ks * 8 + 4 + v], false, false);
-                    lo[v] = r.x;
-                    hi[v] = r.y;
-                }
-                const half8v b0 = __builtin_bit_cast(half8v, lo), b1 = __builtin_bit_cast(half8v, hi);
+        for (int v = 0; v < 4; ++v) exchange(0, 0, v, lo_c, hi_c);
+        half8v a_cur = frag(0);
+        word_setup(1);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int mb = 0; mb < MW; ++mb) {
-                    const half8v a = *(const half8v *)(xb + (size_t)mb * 32 * XROW + d * 32 + ks * 16);
-                    acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b0, acc[mb][0], 0, 0, 0);
-                    acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b1, acc[mb][1], 0, 0, 0);
-                }
+        for (int s = 0; s < STEPS; ++s) {
+            const int mb = s % MW, ks = (s / MW) & 1, d = s / SPW, i = s % SPW;
+            const half8v a_nxt = frag(s + 1 < STEPS ? s + 1 : s);
+            acc[mb][0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur, __builtin_bit_cast(half8v, lo_c), acc[mb][0], 0, 0, 0);
+            acc[mb][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur, __builtin_bit_cast(half8v, hi_c), acc[mb][1], 0, 0, 0);
+            a_cur = a_nxt;
+            __builtin_amdgcn_sched_barrier(0);
+            if (d < 3) {
+#pragma unroll
+                for (int p = i * PPS; p < (i + 1) * PPS; ++p) wp[(d + 1) & 1][p] = hlq_rebuild_pair<Q>(wd, sc, p);
             }
+            // operands of the next k-step: (d, 1) during (d, 0), (d + 1, 0) during (d, 1)
+            const int nd = ks == 0 ? d : d + 1, nks = ks ^ 1;
+            if (nd < 4) {
+#pragma unroll
+                for (int v = mb * XPS; v < (mb + 1) * XPS && v < 4; ++v) exchange(nd, nks, v, lo_n, hi_n);
+            }
+            if (mb == MW - 1) {
+                lo_c = lo_n;
+                hi_c = hi_n;
+                if (i == SPW - 1 && d + 2 < 4) word_setup(d + 2);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
 

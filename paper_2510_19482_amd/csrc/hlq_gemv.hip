@@ -1,14 +1,16 @@
-// hlq_lut_gemv: M = 1 bit-serial LUT GEMV (Sec. 2 "Bit-Serial LUT-Based GEMM", App. B),
-// one launch for one or several independent GEMVs.
+// hlq_lut_gemv, table-lookup formulation: M = 1 bit-serial LUT GEMV (Sec. 2 "Bit-Serial LUT-Based
+// GEMM", App. B), one launch for one or several independent GEMVs; plus the host side (launch
+// plans, grouped launches) of both GEMV formulations -- the matrix-core kernel is in hlq_gemv_mx.hip.
 //
 // Work split.  The unit of work is a wavefront: it owns TN adjacent column tiles (64 columns
 // each, lane <-> column) and a run of consecutive chunks (128 k each), i.e. TN contiguous byte
 // streams of the packed blob.  Per chunk it
 //
-//   build    makes its OWN 32 tables in LDS (T[t][i] = sum_r bit_r(i) x[4t+r], App. B; fp32
-//            entries): lane (t, h) computes entries 8h .. 8h+7 of table t and stores them with
-//            two 128-bit LDS writes; the per-quant-group activation sums come from a DPP
-//            reduction of exact fp32 dot products;
+//   build    makes its OWN 32 tables in LDS (T[t][i] = sum_r bit_r(i) x_r over the four even or
+//            four odd activations of one 8-k window, App. B; fp32 entries): each lane loads its
+//            8-k window (quad of lanes <-> window), takes the even or the odd four and stores
+//            entries 0..7 or 8..15 of that table with two 128-bit LDS writes; the per-quant-group
+//            activation sums come from a DPP reduction of exact fp32 dot products;
 //   consume  per plane and 4-bit slice one LDS lookup + one fp32 add; per (plane, quant group)
 //            one FMA with s_j; per quant group one FMA  z * sum(x)       (Eq. 3 by linearity).
 //

@@ -36,20 +36,25 @@ struct HlqSegScales {
     }
 };
 
-// W^ of the 32 weights of word d of one column (Eq. 3): wp[p] = (W^[32d + 2p], W^[32d + 2p + 1]) as
-// packed fp16.  8 shifts + 16 ANDs per plane and 16 packed FMAs per plane.
+// W^ of weights 2p, 2p+1 of one plane-word set (Eq. 3) as packed fp16: (W^[2p], W^[2p + 1]).
+template <int Q>
+__device__ __forceinline__ uint32_t hlq_rebuild_pair(const uint32_t (&w)[Q], const HlqSegScales<Q> &sc, int p)
+{
+    half2v o = sc.z2;
+#pragma unroll
+    for (int j = 0; j < Q; ++j) {
+        const uint32_t sh = hlq_pair_shift(p) < 0 ? (w[j] >> 1) : (w[j] << (hlq_pair_shift(p) < 0 ? 0 : hlq_pair_shift(p)));
+        const uint32_t m = sh & (hlq_pair_pos(p) == 13 ? 0x20002000u : 0x40004000u);
+        o = __builtin_bit_cast(half2v, m) * (hlq_pair_pos(p) == 13 ? sc.s13[j] : sc.s14[j]) + o;
+    }
+    return __builtin_bit_cast(uint32_t, o);
+}
+
+// W^ of the 32 weights of word d of one column: wp[p] = (W^[32d + 2p], W^[32d + 2p + 1]).
+// 8 shifts + 16 ANDs per plane and 16 packed FMAs per plane.
 template <int Q>
 __device__ __forceinline__ void hlq_rebuild_word(const uint32_t (&w)[Q], const HlqSegScales<Q> &sc, uint32_t (&wp)[16])
 {
 #pragma unroll
-    for (int p = 0; p < 16; ++p) {
-        half2v o = sc.z2;
-#pragma unroll
-        for (int j = 0; j < Q; ++j) {
-            const uint32_t sh = hlq_pair_shift(p) < 0 ? (w[j] >> 1) : (w[j] << (hlq_pair_shift(p) < 0 ? 0 : hlq_pair_shift(p)));
-            const uint32_t m = sh & (hlq_pair_pos(p) == 13 ? 0x20002000u : 0x40004000u);
-            o = __builtin_bit_cast(half2v, m) * (hlq_pair_pos(p) == 13 ? sc.s13[j] : sc.s14[j]) + o;
-        }
-        wp[p] = __builtin_bit_cast(uint32_t, o);
-    }
+    for (int p = 0; p < 16; ++p) wp[p] = hlq_rebuild_pair<Q>(w, sc, p);
 }
