@@ -97,7 +97,7 @@ def set_gemv_plan(tiles_per_wave: int = 0, waves_per_workgroup: int = 0, chunks_
     _check("hlq_set_gemv_plan", lib.hlq_set_gemv_plan(tiles_per_wave, waves_per_workgroup, chunks_per_wave))
 
 
-GEMM_AUTO, GEMM_LUT, GEMM_MFMA = 0, 1, 2
+GEMM_AUTO, GEMM_LUT, GEMM_MFMA, GEMM_MFMA_FP16 = 0, 1, 2, 3
 
 
 def set_gemm_path(path: int = 0) -> None:

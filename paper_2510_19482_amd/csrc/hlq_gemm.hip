@@ -253,7 +253,7 @@ static int g_gemm_path = 0;
 
 hlq_status hlq_gemm_path_override(int path)
 {
-    if (path < 0 || path > 2) return HLQ_ERR_UNSUPPORTED;
+    if (path < 0 || path > 3) return HLQ_ERR_UNSUPPORTED;
     g_gemm_path = path;
     return HLQ_OK;
 }
@@ -261,7 +261,7 @@ hlq_status hlq_gemm_path_override(int path)
 static bool use_mfma(int64_t M)
 {
     if (g_gemm_path == 1) return false;
-    if (g_gemm_path == 2) return true;
+    if (g_gemm_path >= 2) return true;
     // measured on MI355X (8B shapes, q = 2..4, HIP-graph timing): the matrix-core kernels are faster
     // than the lookup kernel from M = 2 on, and the gap grows with M
     return M >= 2;
@@ -271,8 +271,10 @@ size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
 {
     size_t a = hlq_gemm_lut_partial_bytes(dm, M);
     const size_t b = hlq_gemm_mfma_partial_bytes(dm, M), c = hlq_gemm_skinny_partial_bytes(dm, M);
+    const size_t e = hlq_gemm_mx_partial_bytes(dm, M);
     if (b > a) a = b;
     if (c > a) a = c;
+    if (e > a) a = e;
     return a;
 }
 
@@ -280,7 +282,11 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
                            void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
 {
     if (use_mfma(M)) {
-        // a few rows: GEMV-shaped streaming kernel; many rows: tiled kernel with X staged in LDS
+        // as many rows as one pass of the matrix-core GEMV kernel carries (several activation rows per
+        // operand; measured faster than the fp16 streaming kernel up to there, slower with two passes);
+        // then the GEMV-shaped fp16 kernel; many rows: tiled kernel with X staged in LDS
+        if (g_gemm_path != 3 && M <= hlq_gemm_mx_rows_per_pass(dm.G))
+            return hlq_launch_gemm_mx_rows(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
         if (M <= 32) return hlq_launch_gemm_skinny(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
         return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
     }

@@ -474,6 +474,22 @@ GemvPlan plan_gemv(long units)
 int slice_chunks(const GemvPlan &pl) { return (pl.W * pl.cpw + 1) & ~1; }
 int slices_for(const HlqDims &dm, int cps) { return (dm.nchunks + cps - 1) / cps; }
 
+// Work split of one problem for the matrix-core kernel: runs of about cpw chunks for every problem
+// of a launch (wavefronts with longer runs would finish alone, with the memory system half idle):
+// K is cut inside the workgroup first (kw wavefronts per tile), then across workgroups.
+void plan_mx_problem(const HlqDims &dm, int W, int cpw, GemvProb &p)
+{
+    p.kw = 1;
+    while (p.kw * 2 <= W && dm.nchunks / (p.kw * 2) >= cpw) p.kw *= 2;
+    int per_slice = p.kw * cpw;
+    if (per_slice < 4) per_slice = 4;
+    p.nslices = (dm.nchunks + per_slice / 2) / per_slice;   // nearest
+    if (p.nslices < 1) p.nslices = 1;
+    const int tiles_per_wg = W / p.kw;
+    p.ntg = (dm.ntiles + tiles_per_wg - 1) / tiles_per_wg;
+    p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
+}
+
 } // namespace
 
 hlq_status hlq_gemv_path_override(int path)
@@ -558,23 +574,15 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         p.nchunks = dm.nchunks;
         p.ntiles = dm.ntiles;
         p.kw = 1;
+        p.M = 1;
+        p.ldx = p.ldy = 0;
         if (mx) {
-            const int cpw_i = pl.cpw;
-            // Runs of about cpw chunks for every problem of the launch (wavefronts with longer runs would
-            // finish alone, with the memory system half idle): cut K inside the workgroup first (kw
-            // wavefronts per tile), then across workgroups.
-            while (p.kw * 2 <= pl.W && dm.nchunks / (p.kw * 2) >= cpw_i) p.kw *= 2;
-            int per_slice = p.kw * cpw_i;
-            if (per_slice < 4) per_slice = 4;
-            p.nslices = (dm.nchunks + per_slice / 2) / per_slice;   // nearest
-            if (p.nslices < 1) p.nslices = 1;
-            const int tiles_per_wg = pl.W / p.kw;
-            p.ntg = (dm.ntiles + tiles_per_wg - 1) / tiles_per_wg;
+            plan_mx_problem(dm, pl.W, pl.cpw, p);
         } else {
             p.ntg = (dm.ntiles + pl.TN - 1) / pl.TN;
             p.nslices = slices_for(dm, cps);
+            p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
         }
-        p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
         p.blk_begin = (int)blk;
         p.cnt = cnt + cnt_used;
         p.part = part;
@@ -590,7 +598,7 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     const int q = items[0].dm.q, G = items[0].dm.G;
     hlq_status s;
     if (mx) {
-        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, q, G, st);
+        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, 0, q, G, st);
         if (s != HLQ_OK) return s;
         return hlq_hip_status(hipGetLastError());
     }
@@ -602,5 +610,61 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     default: return HLQ_ERR_UNSUPPORTED;
     }
     if (s != HLQ_OK) return s;
+    return hlq_hip_status(hipGetLastError());
+}
+
+// Rows an MX launch can carry for group size G (two row sets).
+int hlq_gemm_mx_rows_per_pass(int G) { return 2 * hlq_gemv_mx_rows_per_set(G); }
+
+size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M)
+{
+    const int cap = hlq_gemm_mx_rows_per_pass(dm.G);
+    const int64_t rows = M < cap ? M : cap;
+    return (size_t)rows * hlq_gemv_partial_bytes(dm);   // slices are never shorter than 4 chunks here either
+}
+
+// Y[M, N] = X[M, K] @ W^ for a few rows with the matrix-core GEMV kernel: passes of up to
+// hlq_gemm_mx_rows_per_pass(G) rows, each streaming the weights once.
+hlq_status hlq_launch_gemm_mx_rows(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
+                                   void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
+{
+    hlq_clear_stale_error();
+    const int rps = hlq_gemv_mx_rows_per_set(dm.G), cap = 2 * rps;
+    const long units = (long)dm.ntiles * dm.nchunks;
+    GemvPlan pl = plan_gemv(units);
+    // measured (8B shapes, q = 4, M = 2..8): short runs on few wavefronts per workgroup for the narrow
+    // shapes, longer runs and eight wavefronts once there are enough tiles
+    pl.W = units < 4096 ? 4 : 8;
+    pl.cpw = units < 4096 ? 2 : 4;
+    if (g_plan_w) pl.W = g_plan_w;
+    if (g_plan_cpw) pl.cpw = g_plan_cpw;
+    while (pl.W & (pl.W - 1)) pl.W &= pl.W - 1;
+    if (pl.W > hlq_gemv_mx_max_waves(dm.q, dm.G)) pl.W = hlq_gemv_mx_max_waves(dm.q, dm.G);
+    const size_t ysz = out == HLQ_OUT_F32 ? 4 : 2;
+    for (int64_t m0 = 0; m0 < M; m0 += cap) {
+        const int rows = (int)(M - m0 < cap ? M - m0 : cap);
+        GemvBatch b;
+        b.count = 1;
+        b.out_f32 = out == HLQ_OUT_F32;
+        GemvProb &p = b.p[0];
+        p.packed = (const char *)packed;
+        p.x = X + (size_t)m0 * ldx;
+        p.y = (char *)Y + (size_t)m0 * ldy * ysz;
+        p.col_bytes = dm.col_bytes;
+        p.N = dm.N;
+        p.nchunks = dm.nchunks;
+        p.ntiles = dm.ntiles;
+        p.M = rows;
+        p.ldx = (long)ldx;
+        p.ldy = (long)ldy;
+        plan_mx_problem(dm, pl.W, pl.cpw, p);
+        p.blk_begin = 0;
+        p.cnt = (int *)ws;
+        p.part = (float *)((char *)ws + HLQ_WS_COUNTER_BYTES);
+        if (p.nslices > 1 && dm.ntiles > HLQ_WS_COUNTER_BYTES / 4) return HLQ_ERR_UNSUPPORTED;
+        for (int i = 1; i < HLQ_MAX_BATCH; ++i) b.p[i] = b.p[0];
+        const hlq_status s = hlq_launch_gemv_mx(b, (unsigned)((long)p.ntg * p.nslices), pl.W, rows <= rps ? 1 : 2, dm.q, dm.G, st);
+        if (s != HLQ_OK) return s;
+    }
     return hlq_hip_status(hipGetLastError());
 }

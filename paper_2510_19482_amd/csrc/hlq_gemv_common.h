@@ -15,6 +15,8 @@ struct GemvProb {
     size_t col_bytes;
     int N, nchunks, ntiles, ntg, nslices, cps, blk_begin;
     int kw;            // matrix-core kernel: wavefronts per tile (runs a slice is cut into)
+    int M;             // matrix-core kernel, batched rows: activation rows; x / y row strides in elements
+    long ldx, ldy;
 };
 
 struct GemvBatch {
@@ -33,5 +35,6 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
 
 // matrix-core formulation (hlq_gemv_mx.hip): W (a power of two) wavefronts per workgroup, kw of them
 // per tile: ntg = ceil(ntiles / (W / kw)) tile groups, one arrival counter per TILE
-hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st);
+hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int q, int G, hipStream_t st);
 int hlq_gemv_mx_max_waves(int q, int G);
+int hlq_gemv_mx_rows_per_set(int G);

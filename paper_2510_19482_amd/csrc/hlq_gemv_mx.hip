@@ -40,6 +40,12 @@
 //             in the wavefront's LDS block in matrix-core k order, one chunk ahead of the MFMAs;
 //   contract  per chunk and column block one MFMA per plane, plus one with the all-ones plane.
 //
+// A few rows at once (small-batch decode, hlq_lut_gemm with M <= 16).  At M = 1 only four of the 16
+// operand rows are in use when a quant group spans the chunk (G >= 128).  The batched instantiation
+// fills them: row 4t + (r * SEG + sg) holds term t of activation row r restricted to segment sg, so
+// one operand carries 4 / SEG activation rows, NS operands ("row sets") carry NS * 4 / SEG rows,
+// and every expanded plane word is used NS times.  Weights are still read once.
+//
 // Lane l loads the four plane words of column l (one 128-bit load per plane, as the lookup kernel
 // does); a 4 x 4 transpose over (16-lane group, word) by v_permlane16_swap / v_permlane32_swap then
 // gives lane l = c + 16 g word g (32 k) of column 16 cb + c for the four column blocks cb -- the
@@ -58,6 +64,9 @@ typedef unsigned short ushort2_t __attribute__((ext_vector_type(2)));
 typedef int int8v __attribute__((ext_vector_type(8)));
 typedef unsigned int uint2v __attribute__((ext_vector_type(2)));
 typedef float float4v __attribute__((ext_vector_type(4)));
+// the scale block in LDS is written as 16-bit values and read back as 32-bit words
+typedef uint16_t __attribute__((may_alias)) u16_alias;
+typedef uint32_t __attribute__((may_alias)) u32_alias;
 
 // Cuts the pair v to three significant bits (the high byte of each fp16 is a bf8 code: sign, exponent,
 // two mantissa bits), stores the two codes at LDS bytes addr + 128 T and addr + 128 T + 4, returns
@@ -82,20 +91,23 @@ __device__ __forceinline__ uint32_t max_dpp(uint32_t v)
     return max(v, moved);
 }
 
-template <int Q, int G>
+template <int Q, int G, int NROW>
 struct MxRegs {
     static constexpr int GS = G < 128 ? G : 128;
     static constexpr int SEG = 128 / GS;
     uint32_t w[Q][4];          // plane j: the four words (32 k each) of column l
     uint16_t mt[SEG][Q + 1];   // lane <-> column l of the tile
-    uint32_t x;                // activations 2l, 2l+1 of the chunk
+    uint32_t x[NROW];          // activations 2l, 2l+1 of the chunk, per activation row
 };
 
 // bytes per column of the transposed scale block in LDS (a multiple of 8)
 constexpr int mx_meta_stride(int Q, int G) { return ((128 / (G < 128 ? G : 128)) * (Q + 1) * 2 + 7) & ~7; }
-constexpr int MX_XT_BYTES = 576;     // four terms x 128 bf8, then 16 zero bytes (padded to 64)
-// per wavefront: activation codes | scales [64][stride] | sums [4][64] fp32
-constexpr int mx_wave_lds(int Q, int G) { return MX_XT_BYTES + 64 * mx_meta_stride(Q, G) + 4 * 64 * 4; }
+// activation rows a kernel instantiation handles: one (GEMV), or NS row sets of 4 / SEG rows
+constexpr int mx_rows(int G, int NS, bool batched) { return batched ? NS * (4 / (128 / (G < 128 ? G : 128))) : 1; }
+// per wavefront: activation codes (per row four terms x 128 bf8; then 16 zero bytes, padded to 64) |
+// scales [64][stride] | sums [row][4][64] fp32
+constexpr int mx_xt_bytes(int nrow) { return nrow * 512 + 64; }
+constexpr int mx_wave_lds(int Q, int G, int nrow) { return mx_xt_bytes(nrow) + 64 * mx_meta_stride(Q, G) + nrow * 4 * 64 * 4; }
 // Register sets of chunk loads per wavefront (chunks in flight + 1).  Two: launches of this kernel
 // have thousands of wavefronts, which together keep far more than the bandwidth-delay product in
 // flight; deeper prefetch only costs registers, i.e. resident wavefronts (measured: 2 beats 3, 4, 6, 8).
@@ -105,14 +117,16 @@ constexpr int mx_nbuf(int, int) { return HLQ_MX_NBUF; }
 constexpr int mx_nbuf(int, int) { return 2; }
 #endif
 
-template <int Q, int G>
+template <int Q, int G, int NS, bool BATCHED>
 __global__ void __launch_bounds__(512)
 hlq_gemv_mx_kernel(const GemvBatch b)
 {
-    using Regs = MxRegs<Q, G>;
+    constexpr int NROW = mx_rows(G, NS, BATCHED);
+    using Regs = MxRegs<Q, G, NROW>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
+    constexpr int RPS = 4 / SEG;   // activation rows one operand can carry
     constexpr int MSTR = mx_meta_stride(Q, G);
-    constexpr int PERW = mx_wave_lds(Q, G);
+    constexpr int PERW = mx_wave_lds(Q, G, NROW);
     constexpr int NBUF = mx_nbuf(Q, G);
     const int W = (int)(blockDim.x >> 6);
     extern __shared__ __attribute__((aligned(256))) char lds[];
@@ -152,11 +166,13 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     uint32_t woff = moff * 8u;   // this lane's 16 bytes inside a plane of a record
     uint32_t xoff = (uint32_t)lane * 4u;
 
-    char *xt = lds + wave * PERW;                     // [term][128] bf8 in matrix-core k order, 16 zero bytes
-    char *meta = xt + MX_XT_BYTES;                    // [column][SEG][Q+1] fp16
-    float *red = (float *)(meta + 64 * MSTR);         // [4][64]
+    char *xt = lds + wave * PERW;                     // [row][term][128] bf8 in matrix-core k order, 16 zero bytes
+    char *meta = xt + mx_xt_bytes(NROW);              // [column][SEG][Q+1] fp16
+    float *red = (float *)(meta + 64 * MSTR);         // [row][4][64]
     constexpr int RSTR = PERW / 4;                    // floats between wavefronts' sums
-    if (lane < 4) ((uint32_t *)(xt + 512))[lane] = 0u;
+    const int M = BATCHED ? P.M : 1;
+    // rows past M are never converted: their codes stay zero
+    for (int i = lane; i < mx_xt_bytes(NROW) / 4; i += 64) ((uint32_t *)xt)[i] = 0u;
 
     auto load_chunk = [&](int ch, Regs &R) {
         // The lane offsets pass through an empty asm: they are re-extended to 64 bits at each use,
@@ -181,33 +197,48 @@ hlq_gemv_mx_kernel(const GemvBatch b)
             for (int r = 0; r <= Q; ++r)
                 if (HLQ_MX_DEBUG < 7 || HLQ_MX_DEBUG > 8) R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
                 else R.mt[sg][r] = 0;
-        R.x = *(const uint32_t *)((const char *)(P.x + (size_t)ch * 128) + xoff);
+#pragma unroll
+        for (int m = 0; m < NROW; ++m)   // rows past M re-read the last row and are ignored
+            R.x[m] = *(const uint32_t *)((const char *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)ch * 128) + xoff);
     };
 
     // ---- scale: largest magnitude of the run's activations (as fp16 bit patterns) --------------------------
     // The activation loads go out BEFORE the weight loads: memory returns a wavefront's loads in
     // order, so the scale is known as soon as x is there, long before the first chunk.
     const int nrun = cend - cbeg;
-    const uint32_t *xr = (const uint32_t *)(P.x + (size_t)cbeg * 128) + lane;
-    uint32_t xu[8];
+    uint32_t xu[NROW][8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) xu[i] = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0u : xr[(size_t)max(min(i, nrun - 1), 0) * 64];
+    for (int m = 0; m < NROW; ++m) {
+        const uint32_t *xr = (const uint32_t *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)cbeg * 128) + lane;
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            xu[m][i] = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0u : xr[(size_t)max(min(i, nrun - 1), 0) * 64];
+    }
 
     // weight loads of the first chunks (an empty run re-reads the slice's first chunk and drops it)
     Regs R[NBUF];
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) load_chunk(max(min(cbeg + i, cend - 1), sbeg), R[i]);
 
-    uint32_t mx = 0;
-    {
+    // per activation row: largest magnitude -> power-of-two scale.  Biased fp16 exponent e of the largest
+    // magnitude: |x| < 2^(e-14); scaling by 2^(29-e) gives |x| < 2^15.  Plane codes are worth 1/2, 1, 2, 2
+    // by register: lane weights 1/2, 1/4, 1/8, 1/8 make every product bit x activation / 4.  The factor
+    // 2^(29-e) (<= 2^29) is applied as two fp16 multiplications.
+    const int r_ = lane & 3;
+    half2_t sw1[NROW], sw2[NROW];
+    float yscale[NROW];
+#pragma unroll
+    for (int m = 0; m < NROW; ++m) {
+        uint32_t mx = 0;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
             mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx),
-                                                                        __builtin_bit_cast(ushort2_t, xu[i] & 0x7fff7fffu)));
-        for (int ci = 8; ci < ((HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0 : nrun); ++ci) {   // runs longer than eight chunks
-            const uint32_t u = xr[(size_t)ci * 64] & 0x7fff7fffu;
-            mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, u)));
-        }
+                                                                        __builtin_bit_cast(ushort2_t, xu[m][i] & 0x7fff7fffu)));
+        if (m < M)
+            for (int ci = 8; ci < ((HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0 : nrun); ++ci) {   // runs longer than eight chunks
+                const uint32_t u = ((const uint32_t *)(P.x + (size_t)m * P.ldx + (size_t)(cbeg + ci) * 128))[lane] & 0x7fff7fffu;
+                mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, u)));
+            }
         mx = max(mx & 0xffffu, mx >> 16);
         mx = max_dpp<0xB1>(mx);          // quad_perm [1,0,3,2]
         mx = max_dpp<0x4E>(mx);          // quad_perm [2,3,0,1]
@@ -215,43 +246,48 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         mx = max_dpp<0x128>(mx);         // row_ror:8: every lane holds its row's maximum
         mx = max_dpp<0x142, 0xa>(mx);    // row_bcast15: rows 1, 3 take rows 0, 2 in
         mx = max_dpp<0x143, 0xc>(mx);    // row_bcast31: row 3 takes row 1 in
+        const uint32_t top = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0x3c00u : (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
+        const int e = (int)(top >> 10);
+        const int k1 = (29 - e) / 2, k2 = (29 - e) - k1 - (r_ == 0 ? 1 : r_ == 1 ? 2 : 3);   // -4 <= k2 <= 14
+        const _Float16 f1 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k1) << 10));
+        const _Float16 f2 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k2) << 10));
+        sw1[m] = (half2_t){f1, f1};
+        sw2[m] = (half2_t){f2, f2};
+        yscale[m] = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + e) << 23);   // 4 * 2^(e-29)
     }
     HLQ_TS(1);
-    const uint32_t top = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0x3c00u : (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
-    // biased fp16 exponent e of the largest magnitude: |x| < 2^(e-14).  Scale by 2^(29-e): |x| < 2^15.
-    // Plane codes are worth 1/2, 1, 2, 2 by register: weights 1/2, 1/4, 1/8, 1/8 make every product
-    // bit x activation / 4.  The factor 2^(29-e) (<= 2^29) is applied as two fp16 multiplications.
-    const int e = (int)(top >> 10);
-    const int r_ = lane & 3;
-    const int k1 = (29 - e) / 2, k2 = (29 - e) - k1 - (r_ == 0 ? 1 : r_ == 1 ? 2 : 3);   // -4 <= k2 <= 14
-    const _Float16 f1 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k1) << 10));
-    const _Float16 f2 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k2) << 10));
-    const half2_t sw1 = {f1, f1}, sw2 = {f2, f2};
-    const float yscale = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + e) << 23);   // 4 * 2^(e-29)
 
     // ---- activation role: this lane converts x[2l], x[2l+1] of a chunk.  Weight k0 = 2 (l & 15) + h of
     // block g is plane bit (l & 15) + 16 h, i.e. register r = l & 3, nibble ((l >> 2) & 3) + 4 h of the
     // expanded word: matrix-core k index 32 g + 8 r + nibble.
     const uint32_t xt_wa = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)xt +
                            (uint32_t)(32 * g + 8 * r_ + ((lane >> 2) & 3));
-    // ---- operand role: row (lane & 15) = 4 t + sg of the activation operand, 16-k runs [16 g, 16 g + 16)
-    // and [64 + 16 g, ...) of the chunk; a run outside segment sg reads the zero bytes
-    const int at = (lane & 15) >> 2, asg = lane & 3;
-    const char *a_src[2];
+    // ---- operand role: row (lane & 15) = 4 t + s of the activation operand, s = r * SEG + sg (activation
+    // row r of the set, segment sg); 16-k runs [16 g, 16 g + 16) and [64 + 16 g, ...) of the chunk; a run
+    // outside segment sg -- or a row the instantiation does not carry -- reads the zero bytes
+    const int at = (lane & 15) >> 2, as = lane & 3;
+    const char *a_src[NS][2];
 #pragma unroll
-    for (int hh = 0; hh < 2; ++hh) {
-        const int blk = 2 * hh + (g >> 1);       // 32-k block the run lies in
-        const bool on = asg < SEG && (blk * 32) / GS == asg;
-        a_src[hh] = xt + (on ? 128 * at + 64 * hh + 16 * g : 512);
-    }
+    for (int set = 0; set < NS; ++set)
+#pragma unroll
+        for (int hh = 0; hh < 2; ++hh) {
+            const int blk = 2 * hh + (g >> 1);       // 32-k block the run lies in
+            const int r = as / SEG, sg = as % SEG;
+            const bool on = set * RPS + r < NROW && (blk * 32) / GS == sg;
+            a_src[set][hh] = xt + (on ? (set * RPS + r) * 512 + 128 * at + 64 * hh + 16 * g : NROW * 512);
+        }
 
-    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    float acc[NROW][4];
+#pragma unroll
+    for (int m = 0; m < NROW; ++m)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[m][cb] = 0.f;
     const float4v zero4 = {0.f, 0.f, 0.f, 0.f};
 
     // Operands that come through LDS, fetched one chunk ahead: the activation operand and, per column
     // block, the scales of this lane's column (MSTR bytes, fp16).
     struct Pre {
-        int8v A;
+        int8v A[NS];
         uint32_t m[4][MSTR / 4];
     };
     auto scale_of = [](const uint32_t (&m)[MSTR / 4], int i) -> float {   // i-th fp16 of a scale record
@@ -260,25 +296,31 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     };
     auto prefetch = [&](const Regs &Rn, Pre &pn) {
         // activations -> four bf8 terms (bytes = high bytes of fp16 values with three significant bits)
-        {
-            half2_t v = (__builtin_bit_cast(half2_t, Rn.x) * sw1) * sw2;   // exact: powers of two, in range
-            v = put_term<0>(xt_wa, v);
-            v = put_term<1>(xt_wa, v);
-            v = put_term<2>(xt_wa, v);
-            (void)put_term<3>(xt_wa, v);
+#pragma unroll
+        for (int m = 0; m < NROW; ++m) {
+            if (m >= M) break;
+            half2_t v = (__builtin_bit_cast(half2_t, Rn.x[m]) * sw1[m]) * sw2[m];   // exact: powers of two, in range
+            const uint32_t addr = xt_wa + (uint32_t)(m * 512);
+            v = put_term<0>(addr, v);
+            v = put_term<1>(addr, v);
+            v = put_term<2>(addr, v);
+            (void)put_term<3>(addr, v);
         }
         // scales: lane <-> column to LDS, read back per column block
 #pragma unroll
         for (int sg = 0; sg < SEG; ++sg)
 #pragma unroll
-            for (int r = 0; r <= Q; ++r) ((uint16_t *)(meta + lane * MSTR))[sg * (Q + 1) + r] = Rn.mt[sg][r];
-        const uint4 alo = *(const uint4 *)a_src[0];
-        const uint4 ahi = *(const uint4 *)a_src[1];
-        pn.A = (int8v){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, (int)ahi.z, (int)ahi.w};
+            for (int r = 0; r <= Q; ++r) ((u16_alias *)(meta + lane * MSTR))[sg * (Q + 1) + r] = Rn.mt[sg][r];
+#pragma unroll
+        for (int set = 0; set < NS; ++set) {
+            const uint4 alo = *(const uint4 *)a_src[set][0];
+            const uint4 ahi = *(const uint4 *)a_src[set][1];
+            pn.A[set] = (int8v){(int)alo.x, (int)alo.y, (int)alo.z, (int)alo.w, (int)ahi.x, (int)ahi.y, (int)ahi.z, (int)ahi.w};
+        }
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-            for (int i = 0; i < MSTR / 4; ++i) pn.m[cb][i] = ((const uint32_t *)(meta + (16 * cb + c) * MSTR))[i];
+            for (int i = 0; i < MSTR / 4; ++i) pn.m[cb][i] = ((const u32_alias *)(meta + (16 * cb + c) * MSTR))[i];
     };
     auto expand = [](uint32_t w) -> int8v {   // plane word -> 32 fp4 codes (bit 4p+r -> nibble p of register r)
         return (int8v){(int)(w & 0x11111111u), (int)(w & 0x22222222u), (int)(w & 0x44444444u),
@@ -297,14 +339,24 @@ hlq_gemv_mx_kernel(const GemvBatch b)
             for (int j = 0; j < Q; ++j) m ^= R.w[j][0] ^ R.w[j][1] ^ R.w[j][2] ^ R.w[j][3];
 #pragma unroll
             for (int r = 0; r <= Q; ++r) m ^= R.mt[0][r];
-            acc[0] += (float)m;
+            acc[0][0] += (float)m;
             load_chunk(ch_reload, R);
             return;
         }
         constexpr int NI = 4 * Q;   // items; item n: column block n / Q, plane n % Q
+        // result register s of an MFMA belongs to activation row s / SEG of the set and segment s % SEG
+        auto apply = [&](int set, const float4v &d, int cb, int which) {
+#pragma unroll
+            for (int sl = 0; sl < 4; ++sl) {
+                const int r = sl / SEG, sg = sl % SEG;
+                if (set * RPS + r < NROW) acc[set * RPS + r][cb] += scale_of(p.m[cb], sg * (Q + 1) + which) * d[sl];
+            }
+        };
         // segment sums of x for the zero points: all-ones plane
         const int8v ones = {0x11111111, 0x22222222, 0x44444444, 0x44444444, 0, 0, 0, 0};
-        const float4v xs = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A, ones, zero4, 1, 4, 0, 0, 0, 0);
+        float4v xs[NS];
+#pragma unroll
+        for (int set = 0; set < NS; ++set) xs[set] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A[set], ones, zero4, 1, 4, 0, 0, 0, 0);
         // 4 x 4 transpose over (16-lane group, word): afterwards wt[j][cb] of lane (c, g) is word g of
         // column 16 cb + c
         uint32_t wt[Q][4];
@@ -320,34 +372,34 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         // ahead): refill it now, before the MFMAs, so the next request is not held up by them
         if (HLQ_MX_DEBUG != 2) load_chunk(ch_reload, R);
         int8v B = expand(wt[0][0]);
-        float4v d[3];
+        float4v d[NS][3];
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int n = 0; n < NI; ++n) {
-            d[n % 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A, B, zero4, 1, 4, 0, 0, 0, 0);
+#pragma unroll
+            for (int set = 0; set < NS; ++set)
+                d[set][n % 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A[set], B, zero4, 1, 4, 0, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (n + 1 < NI) B = expand(wt[(n + 1) % Q][(n + 1) / Q]);
             if (n >= 1) {
-                const int cb = (n - 1) / Q, j = (n - 1) % Q;
 #pragma unroll
-                for (int sg = 0; sg < SEG; ++sg) acc[cb] += scale_of(p.m[cb], sg * (Q + 1) + j) * d[(n - 1) % 3][sg];
-                // keeps all four result registers allocated up to here: if the unused ones were handed
-                // to the next operand while the MFMA is in flight, every write to them would have to
-                // wait for it
-                asm volatile("" ::"v"(d[(n - 1) % 3]));
+                for (int set = 0; set < NS; ++set) {
+                    apply(set, d[set][(n - 1) % 3], (n - 1) / Q, (n - 1) % Q);
+                    // keeps all four result registers allocated up to here: if the unused ones were handed
+                    // to the next operand while the MFMA is in flight, every write to them would have to
+                    // wait for it
+                    asm volatile("" ::"v"(d[set][(n - 1) % 3]));
+                }
             }
             if (n == 1) prefetch(Rn, pn);
             __builtin_amdgcn_sched_barrier(0);
         }
-        {
-            const int cb = (NI - 1) / Q, j = (NI - 1) % Q;
 #pragma unroll
-            for (int sg = 0; sg < SEG; ++sg) acc[cb] += scale_of(p.m[cb], sg * (Q + 1) + j) * d[(NI - 1) % 3][sg];
+        for (int set = 0; set < NS; ++set) {
+            apply(set, d[set][(NI - 1) % 3], (NI - 1) / Q, (NI - 1) % Q);
+#pragma unroll
+            for (int cb = 0; cb < 4; ++cb) apply(set, xs[set], cb, Q);
         }
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-            for (int sg = 0; sg < SEG; ++sg) acc[cb] += scale_of(p.m[cb], sg * (Q + 1) + Q) * xs[sg];
     };
 
     // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
@@ -364,12 +416,14 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     HLQ_TS(3);
     // ---- undo the run's scaling; add the four terms (lane groups) and the tile's KW runs ---------------------
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) red[cb * 64 + lane] = acc[cb] * yscale;
+    for (int m = 0; m < NROW; ++m)
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) red[(m * 4 + cb) * 64 + lane] = acc[m][cb] * yscale[m];
     if (HLQ_MX_DEBUG != 8) __syncthreads();
     HLQ_TS(4);
 #if HLQ_MX_DEBUG == 9
     if (lane == 0 && wave == 0) {
-        ts[5] = (long long)acc[0];
+        ts[5] = (long long)acc[0][0];
         long long *dst = (long long *)((char *)b.p[0].cnt + 65536) + (size_t)(blockIdx.x % 1000) * 8;
         for (int i = 0; i < 6; ++i) dst[i] = ts[i];
         dst[6] = pi;
@@ -377,55 +431,77 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     }
 #endif
     if (part != 0 || !tile_ok) return;
-    float y = 0.f;
-    for (int w2 = 0; w2 < KW; ++w2)
+    float y[NROW];
 #pragma unroll
-        for (int g2 = 0; g2 < 4; ++g2) y += red[w2 * RSTR + (lane >> 4) * 64 + (lane & 15) + 16 * g2];
+    for (int m = 0; m < NROW; ++m) {
+        y[m] = 0.f;
+        for (int w2 = 0; w2 < KW; ++w2)
+#pragma unroll
+            for (int g2 = 0; g2 < 4; ++g2) y[m] += red[w2 * RSTR + (m * 4 + (lane >> 4)) * 64 + (lane & 15) + 16 * g2];
+    }
     const bool col_ok = lane < tw;
     const size_t n = (size_t)tile * HLQ_TILE_N + lane;
+    const size_t ldy = BATCHED ? (size_t)P.ldy : 0;
 
     if (P.nslices == 1 || HLQ_MX_DEBUG == 5) {
-        if (col_ok) store_out(P.y, n, y, b.out_f32);
+#pragma unroll
+        for (int m = 0; m < NROW; ++m)
+            if (col_ok && m < M) store_out(P.y, m * ldy + n, y[m], b.out_f32);
         return;
     }
-    // ---- split-K across workgroups: write-through partials, arrival counter, last one adds in slice order
-    if (col_ok) __hip_atomic_store(&P.part[(size_t)slice * P.N + n], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // ---- split-K across workgroups: write-through partials [slice][row][N], arrival counter, last one adds
+    // in slice order
+    const size_t MN = (size_t)M * P.N;
+#pragma unroll
+    for (int m = 0; m < NROW; ++m)
+        if (col_ok && m < M)
+            __hip_atomic_store(&P.part[(size_t)slice * MN + (size_t)m * P.N + n], y[m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     int old = 0;
     if (lane == 0) old = __hip_atomic_fetch_add(&P.cnt[tile], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     old = __builtin_amdgcn_readfirstlane(old);
     if (old != P.nslices - 1) return;
     if (col_ok) {
-        float a = 0.f;
-        int sl = 0;
-        for (; sl + 4 <= P.nslices; sl += 4) {
-            const float v0 = __hip_atomic_load(&P.part[(size_t)(sl + 0) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float v1 = __hip_atomic_load(&P.part[(size_t)(sl + 1) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float v2 = __hip_atomic_load(&P.part[(size_t)(sl + 2) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const float v3 = __hip_atomic_load(&P.part[(size_t)(sl + 3) * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            a = (((a + v0) + v1) + v2) + v3;
+#pragma unroll
+        for (int m = 0; m < NROW; ++m) {
+            if (m >= M) break;
+            const float *src = &P.part[(size_t)m * P.N + n];
+            float a = 0.f;
+            int sl = 0;
+            for (; sl + 4 <= P.nslices; sl += 4) {
+                const float v0 = __hip_atomic_load(src + (size_t)(sl + 0) * MN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float v1 = __hip_atomic_load(src + (size_t)(sl + 1) * MN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float v2 = __hip_atomic_load(src + (size_t)(sl + 2) * MN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float v3 = __hip_atomic_load(src + (size_t)(sl + 3) * MN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                a = (((a + v0) + v1) + v2) + v3;
+            }
+            for (; sl < P.nslices; ++sl) a += __hip_atomic_load(src + (size_t)sl * MN, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            store_out(P.y, m * ldy + n, a, b.out_f32);
         }
-        for (; sl < P.nslices; ++sl)
-            a += __hip_atomic_load(&P.part[(size_t)sl * P.N + n], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        store_out(P.y, n, a, b.out_f32);
     }
     if (lane == 0) __hip_atomic_store(&P.cnt[tile], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int Q, int G>
-void launch_qg(const GemvBatch &b, unsigned nblocks, int W, hipStream_t st)
+void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int nsets, hipStream_t st)
 {
-    hlq_gemv_mx_kernel<Q, G><<<nblocks, dim3(64 * W), (size_t)W * mx_wave_lds(Q, G), st>>>(b);
+    const dim3 blk(64 * W);
+    if (nsets == 0)
+        hlq_gemv_mx_kernel<Q, G, 1, false><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, 1), st>>>(b);
+    else if (nsets == 1)
+        hlq_gemv_mx_kernel<Q, G, 1, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 1, true)), st>>>(b);
+    else
+        hlq_gemv_mx_kernel<Q, G, 2, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 2, true)), st>>>(b);
 }
 
 template <int Q>
-hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, hipStream_t st)
+hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, int nsets, hipStream_t st)
 {
     switch (G) {
-    case 32: launch_qg<Q, 32>(b, nblocks, W, st); return HLQ_OK;
-    case 64: launch_qg<Q, 64>(b, nblocks, W, st); return HLQ_OK;
-    case 128: launch_qg<Q, 128>(b, nblocks, W, st); return HLQ_OK;
-    case 256: launch_qg<Q, 256>(b, nblocks, W, st); return HLQ_OK;
+    case 32: launch_qg<Q, 32>(b, nblocks, W, nsets, st); return HLQ_OK;
+    case 64: launch_qg<Q, 64>(b, nblocks, W, nsets, st); return HLQ_OK;
+    case 128: launch_qg<Q, 128>(b, nblocks, W, nsets, st); return HLQ_OK;
+    case 256: launch_qg<Q, 256>(b, nblocks, W, nsets, st); return HLQ_OK;
     }
     return HLQ_ERR_UNSUPPORTED;
 }
@@ -433,15 +509,18 @@ hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, hipStrea
 } // namespace
 
 int hlq_gemv_mx_max_waves(int, int) { return 8; }
+int hlq_gemv_mx_rows_per_set(int G) { return mx_rows(G, 1, true); }
 
-hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st)
+// nsets: 0 = GEMV (one activation row per problem), 1 / 2 = batched rows with that many row sets
+// (every problem's M must fit nsets * hlq_gemv_mx_rows_per_set(G)).
+hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int q, int G, hipStream_t st)
 {
-    if (W < 1 || W > 8 || (W & (W - 1))) return HLQ_ERR_UNSUPPORTED;
+    if (W < 1 || W > 8 || (W & (W - 1)) || nsets < 0 || nsets > 2) return HLQ_ERR_UNSUPPORTED;
     switch (q) {
-    case 1: return launch_q<1>(G, b, nblocks, W, st);
-    case 2: return launch_q<2>(G, b, nblocks, W, st);
-    case 3: return launch_q<3>(G, b, nblocks, W, st);
-    case 4: return launch_q<4>(G, b, nblocks, W, st);
+    case 1: return launch_q<1>(G, b, nblocks, W, nsets, st);
+    case 2: return launch_q<2>(G, b, nblocks, W, nsets, st);
+    case 3: return launch_q<3>(G, b, nblocks, W, nsets, st);
+    case 4: return launch_q<4>(G, b, nblocks, W, nsets, st);
     }
     return HLQ_ERR_UNSUPPORTED;
 }

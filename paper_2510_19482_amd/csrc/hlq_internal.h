@@ -113,6 +113,10 @@ size_t hlq_gemm_skinny_partial_bytes(const HlqDims &dm, int64_t M);
 hlq_status hlq_launch_gemm_skinny(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
                                   int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_gemm_path_override(int path);
+int hlq_gemm_mx_rows_per_pass(int G);
+size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M);
+hlq_status hlq_launch_gemm_mx_rows(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
+                                   void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 
 // HLQ_VERBOSE=1 in the environment prints the runtime's message for a failed launch to stderr.
 static inline hlq_status hlq_hip_status(hipError_t e)

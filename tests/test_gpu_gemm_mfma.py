@@ -14,14 +14,16 @@ from gpu_util import TOL, dev, gemm_gpu, pack_on_gpu
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True)
-def mfma_path():
-    B.set_gemm_path(B.GEMM_MFMA)
+@pytest.fixture(autouse=True, params=["matrix-core", "fp16-rebuild-only"])
+def mfma_path(request):
+    # "matrix-core" sends a few rows to the GEMV kernel with several activation rows per operand,
+    # "fp16-rebuild-only" keeps them on the fp16 streaming kernel; larger M is the same in both
+    B.set_gemm_path(B.GEMM_MFMA if request.param == "matrix-core" else B.GEMM_MFMA_FP16)
     yield
     B.set_gemm_path(B.GEMM_AUTO)
 
 
-@pytest.mark.parametrize("M", [2, 17, 32, 33, 64, 65, 100, 128, 200])
+@pytest.mark.parametrize("M", [2, 3, 4, 5, 8, 9, 16, 17, 32, 33, 64, 65, 100, 128, 200])
 @pytest.mark.parametrize("q,G", [(2, 128), (3, 128), (4, 64), (1, 32), (2, 256)])
 def test_mfma_vs_oracle(M, q, G):
     K, N = 1280, 584          # 10 chunks; 9 full tiles + a 8-column tail; 3 column groups
@@ -35,6 +37,32 @@ def test_mfma_vs_oracle(M, q, G):
     assert err.max() <= 1e-3, err.max()
     Y16 = gemm_gpu(d, packed, X, out_f32=False)
     assert O.row_rel_err(Y16, ref).max() <= TOL
+
+
+@pytest.mark.parametrize("M,q,G", [(4, 4, 128), (7, 2, 128), (16, 4, 128), (3, 3, 64), (8, 2, 64), (2, 2, 32), (4, 1, 32)])
+def test_few_rows_strides_long_k_and_repeatability(M, q, G):
+    # K long enough that it is cut across workgroups; X and Y with leading dimensions; rows of very
+    # different magnitude (one common power-of-two scale serves all rows of a pass)
+    K, N = 8192, 200
+    codes, S, Z = synth.make_weight(K, N, q, G, "fewrows")
+    X = synth.make_x(M, K, "fewrows", outliers=True).astype(np.float64)
+    X[0] *= 2.0 ** -9
+    if M > 2:
+        X[M - 1] *= 2.0 ** 6
+    X = X.astype(np.float16)
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    ref = c_oracle.gemm_f64(X, codes, S, Z, q, G)
+    Xd = torch.zeros(M, K + 24, dtype=torch.float16, device="cuda")
+    Xd[:, :K] = dev(X)
+    Yd = torch.full((M, N + 8), 5.0, dtype=torch.float32, device="cuda")
+    outs = []
+    for rep in range(2):
+        B.hlq_lut_gemm(d, packed, Xd[:, :K], Y=Yd[:, :N], out_f32=True)
+        torch.cuda.synchronize()
+        outs.append(Yd.cpu().numpy().astype(np.float64))
+    assert np.array_equal(outs[0], outs[1])
+    assert np.all(outs[0][:, N:] == 5.0)
+    assert O.row_rel_err(outs[0][:, :N], ref).max() <= 1e-3
 
 
 def test_mfma_identity_rows_read_back_weights():
