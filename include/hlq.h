@@ -118,6 +118,20 @@ HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const vo
                                       const uint16_t *const *x, void *const *y, hlq_out_dtype out,
                                       void *ws, size_t ws_bytes, void *stream);
 
+/* Several independent small-batch products Y_i[M, N_i] = X_i[M, K_i] @ W^_i in one launch (the
+ * GEMMs of a decoder layer at M = 2..8: Sec. 2, batched rows).  All problems share q, G and M;
+ * X_i row-major with leading dimension ldx[i] >= K_i (a multiple of 8 for M > 1), Y_i with
+ * ldy[i] >= N_i; descs, packed, X, ldx, Y, ldy are host arrays of `count` (1..8) entries.  When M
+ * exceeds what one pass of the few-rows kernel carries (8 rows at G >= 128, 4 at G = 64, 2 at
+ * G = 32), or the lookup formulation is forced, the problems are run one after the other on the
+ * stream instead.  M = 0 is a no-op.
+ *   ws / ws_bytes: workspace of at least hlq_gemm_batch_workspace_bytes(count, descs, M). */
+HLQ_API hlq_status hlq_gemm_batch_workspace_bytes(int count, const hlq_desc *descs, int64_t M, size_t *bytes);
+HLQ_API hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const void *const *packed,
+                                      const uint16_t *const *X, int64_t M, const int64_t *ldx, void *const *Y,
+                                      const int64_t *ldy, hlq_out_dtype out, void *ws, size_t ws_bytes,
+                                      void *stream);
+
 /* Tuning knob (process-wide, not thread-safe; for benchmarks and tests): force the launch shape
  * of the GEMV kernel -- column tiles per wavefront (1 or 2), wavefronts per workgroup (1..16),
  * chunks of 128 k per wavefront -- instead of the built-in choice.  0 leaves a value automatic.

@@ -59,6 +59,12 @@ def _load() -> ctypes.CDLL:
     lib.hlq_batch_workspace_bytes.argtypes = [ctypes.c_int, dp, szp]
     lib.hlq_workspace_init.restype = ctypes.c_int
     lib.hlq_workspace_init.argtypes = [vp, sz, vp]
+    lib.hlq_gemm_batch_workspace_bytes.restype = ctypes.c_int
+    lib.hlq_gemm_batch_workspace_bytes.argtypes = [ctypes.c_int, dp, ctypes.c_int64, szp]
+    lib.hlq_lut_gemm_batch.restype = ctypes.c_int
+    lib.hlq_lut_gemm_batch.argtypes = [ctypes.c_int, dp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.c_int64,
+                                       ctypes.POINTER(ctypes.c_int64), ctypes.POINTER(vp),
+                                       ctypes.POINTER(ctypes.c_int64), ctypes.c_int, vp, ctypes.c_size_t, vp]
     lib.hlq_lut_gemv_batch.restype = ctypes.c_int
     lib.hlq_lut_gemv_batch.argtypes = [ctypes.c_int, dp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                        ctypes.POINTER(vp), ctypes.c_int, vp, sz, vp]
@@ -198,6 +204,34 @@ class GemvBatch:
         _check("hlq_lut_gemv_batch", lib.hlq_lut_gemv_batch(
             self.n, self.descs, self.packed, self.xs, self.ys, self.out, _ptr(self.ws),
             self.ws.numel(), _stream_ptr(stream)))
+
+
+class GemmBatch:
+    """Pre-marshalled arguments of one hlq_lut_gemm_batch call: Y_i[M, N_i] = X_i[M, K_i] @ W^_i."""
+
+    def __init__(self, descs, packed, Xs, Ys, out_f32=False, ws=None):
+        n = len(descs)
+        self.n = n
+        self.M = int(Xs[0].shape[0])
+        self.descs = (HlqDesc * n)(*descs)
+        self.packed = (ctypes.c_void_p * n)(*[_ptr(p) for p in packed])
+        self.Xs = (ctypes.c_void_p * n)(*[_ptr(x) for x in Xs])
+        self.Ys = (ctypes.c_void_p * n)(*[_ptr(y) for y in Ys])
+        self.ldx = (ctypes.c_int64 * n)(*[max(int(x.stride(0)), d.K) for x, d in zip(Xs, descs)])
+        self.ldy = (ctypes.c_int64 * n)(*[max(int(y.stride(0)), d.N) for y, d in zip(Ys, descs)])
+        self.out = HLQ_OUT_F32 if out_f32 else HLQ_OUT_F16
+        if ws is None:
+            w = ctypes.c_size_t()
+            _check("hlq_gemm_batch_workspace_bytes",
+                   lib.hlq_gemm_batch_workspace_bytes(n, self.descs, self.M, ctypes.byref(w)))
+            ws = _new_workspace(w.value, Xs[0].device)
+        self.ws = ws
+        self._keep = (list(packed), list(Xs), list(Ys))
+
+    def launch(self, stream=None):
+        _check("hlq_lut_gemm_batch", lib.hlq_lut_gemm_batch(
+            self.n, self.descs, self.packed, self.Xs, self.M, self.ldx, self.Ys, self.ldy, self.out,
+            _ptr(self.ws), self.ws.numel(), _stream_ptr(stream)))
 
 
 def hlq_lut_gemv(desc: HlqDesc, packed, x, y=None, out_f32: bool = False, ws=None, stream=None):

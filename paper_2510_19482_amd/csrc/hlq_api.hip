@@ -97,6 +97,22 @@ hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, size_t *b
     return HLQ_OK;
 }
 
+hlq_status hlq_gemm_batch_workspace_bytes(int count, const hlq_desc *descs, int64_t M, size_t *bytes)
+{
+    if (!descs || !bytes) return HLQ_ERR_NULL;
+    if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
+    if (M < 0) return HLQ_ERR_BAD_STRIDE;
+    size_t b = HLQ_WS_COUNTER_BYTES;
+    for (int i = 0; i < count; ++i) {
+        HlqDims dm;
+        hlq_status s = hlq_check_desc(&descs[i], &dm);
+        if (s != HLQ_OK) return s;
+        b += M <= 1 ? hlq_gemv_partial_bytes(dm) : hlq_gemm_partial_bytes(dm, M);
+    }
+    *bytes = (b + 255u) & ~(size_t)255u;
+    return HLQ_OK;
+}
+
 hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream)
 {
     if (!ws) return HLQ_ERR_NULL;
@@ -178,6 +194,47 @@ hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const void *cons
     }
     if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
     return hlq_launch_gemv_batch(count, items, out, ws, (hipStream_t)stream);
+}
+
+hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const void *const *packed,
+                              const uint16_t *const *X, int64_t M, const int64_t *ldx, void *const *Y,
+                              const int64_t *ldy, hlq_out_dtype out, void *ws, size_t ws_bytes, void *stream)
+{
+    if (!descs || !packed || !X || !Y || !ldx || !ldy || !ws) return HLQ_ERR_NULL;
+    if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
+    if (out != HLQ_OUT_F16 && out != HLQ_OUT_F32) return HLQ_ERR_UNSUPPORTED;
+    if (M < 0) return HLQ_ERR_BAD_STRIDE;
+    if (misaligned(ws, 16)) return HLQ_ERR_BAD_STRIDE;
+    HlqGemvItem items[HLQ_MAX_BATCH];
+    size_t need = HLQ_WS_COUNTER_BYTES;
+    for (int i = 0; i < count; ++i) {
+        hlq_status s = hlq_check_desc(&descs[i], &items[i].dm);
+        if (s != HLQ_OK) return s;
+        if (descs[i].q != descs[0].q || descs[i].G != descs[0].G) return HLQ_ERR_UNSUPPORTED;
+        if (ldx[i] < items[i].dm.K || ldy[i] < items[i].dm.N || (M > 1 && ldx[i] % 8 != 0)) return HLQ_ERR_BAD_STRIDE;
+        if (M == 0) continue;
+        if (!packed[i] || !X[i] || !Y[i]) return HLQ_ERR_NULL;
+        if (misaligned(packed[i], 16) || misaligned(X[i], 16) || misaligned(Y[i], out == HLQ_OUT_F32 ? 4 : 2))
+            return HLQ_ERR_BAD_STRIDE;
+        items[i].packed = packed[i];
+        items[i].x = X[i];
+        items[i].y = Y[i];
+        items[i].M = (int)(M < 1024 ? M : 1024);
+        items[i].ldx = (long)ldx[i];
+        items[i].ldy = (long)ldy[i];
+        need += M <= 1 ? hlq_gemv_partial_bytes(items[i].dm) : hlq_gemm_partial_bytes(items[i].dm, M);
+    }
+    if (M == 0) return HLQ_OK;
+    if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
+    // one launch when the few-rows kernel carries M rows and the lookup formulation is not forced;
+    // otherwise the problems run one after the other on the stream, sharing the workspace
+    if (M == 1 || (M <= hlq_gemm_mx_rows_per_pass(items[0].dm.G) && hlq_gemm_uses_mx_rows(M)))
+        return hlq_launch_gemv_batch(count, items, out, ws, (hipStream_t)stream);
+    for (int i = 0; i < count; ++i) {
+        hlq_status s = hlq_launch_gemm(items[i].dm, packed[i], X[i], M, ldx[i], Y[i], ldy[i], out, ws, (hipStream_t)stream);
+        if (s != HLQ_OK) return s;
+    }
+    return HLQ_OK;
 }
 
 hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uint16_t *X, int64_t M,

@@ -532,7 +532,19 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     long units = 0;
     for (int i = 0; i < count; ++i) units += (long)items[i].dm.ntiles * items[i].dm.nchunks;
     GemvPlan pl = plan_gemv(units);
-    const bool mx = use_mx();
+    const int rows = items[0].M;
+    for (int i = 1; i < count; ++i)
+        if (items[i].M != rows) return HLQ_ERR_UNSUPPORTED;
+    if (rows < 1 || rows > hlq_gemm_mx_rows_per_pass(items[0].dm.G)) return HLQ_ERR_UNSUPPORTED;
+    const bool mx = use_mx() || rows > 1;   // several activation rows exist in the matrix-core kernel only
+    if (rows > 1) {
+        // measured (8B shapes, q = 4, M = 2..8): short runs on few wavefronts per workgroup for narrow
+        // launches, longer runs and eight wavefronts once there are enough tiles
+        pl.W = units < 4096 ? 4 : 8;
+        pl.cpw = units < 4096 ? 2 : units < 12000 ? 4 : 6;
+        if (g_plan_w) pl.W = g_plan_w;
+        if (g_plan_cpw) pl.cpw = g_plan_cpw;
+    }
     {
         const int q0 = items[0].dm.q, G0 = items[0].dm.G;
         if (mx || !gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
@@ -574,8 +586,9 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         p.nchunks = dm.nchunks;
         p.ntiles = dm.ntiles;
         p.kw = 1;
-        p.M = 1;
-        p.ldx = p.ldy = 0;
+        p.M = rows;
+        p.ldx = items[order[i]].ldx;
+        p.ldy = items[order[i]].ldy;
         if (mx) {
             plan_mx_problem(dm, pl.W, pl.cpw, p);
         } else {
@@ -589,7 +602,7 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         blk += (long)p.ntg * p.nslices;
         if (p.nslices > 1) {
             cnt_used += mx ? dm.ntiles : p.ntg;
-            part += (size_t)p.nslices * dm.N;
+            part += (size_t)p.nslices * dm.N * rows;
         }
     }
     for (int i = count; i < HLQ_MAX_BATCH; ++i) b.p[i] = b.p[0];
@@ -598,7 +611,8 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     const int q = items[0].dm.q, G = items[0].dm.G;
     hlq_status s;
     if (mx) {
-        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, 0, q, G, st);
+        const int nsets = rows == 1 ? 0 : rows <= hlq_gemv_mx_rows_per_set(G) ? 1 : 2;
+        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, nsets, q, G, st);
         if (s != HLQ_OK) return s;
         return hlq_hip_status(hipGetLastError());
     }
@@ -623,48 +637,18 @@ size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M)
     return (size_t)rows * hlq_gemv_partial_bytes(dm);   // slices are never shorter than 4 chunks here either
 }
 
-// Y[M, N] = X[M, K] @ W^ for a few rows with the matrix-core GEMV kernel: passes of up to
-// hlq_gemm_mx_rows_per_pass(G) rows, each streaming the weights once.
+// Y[M, N] = X[M, K] @ W^ for as many rows as one pass of the matrix-core GEMV kernel carries.
 hlq_status hlq_launch_gemm_mx_rows(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
                                    void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
 {
-    hlq_clear_stale_error();
-    const int rps = hlq_gemv_mx_rows_per_set(dm.G), cap = 2 * rps;
-    const long units = (long)dm.ntiles * dm.nchunks;
-    GemvPlan pl = plan_gemv(units);
-    // measured (8B shapes, q = 4, M = 2..8): short runs on few wavefronts per workgroup for the narrow
-    // shapes, longer runs and eight wavefronts once there are enough tiles
-    pl.W = units < 4096 ? 4 : 8;
-    pl.cpw = units < 4096 ? 2 : 4;
-    if (g_plan_w) pl.W = g_plan_w;
-    if (g_plan_cpw) pl.cpw = g_plan_cpw;
-    while (pl.W & (pl.W - 1)) pl.W &= pl.W - 1;
-    if (pl.W > hlq_gemv_mx_max_waves(dm.q, dm.G)) pl.W = hlq_gemv_mx_max_waves(dm.q, dm.G);
-    const size_t ysz = out == HLQ_OUT_F32 ? 4 : 2;
-    for (int64_t m0 = 0; m0 < M; m0 += cap) {
-        const int rows = (int)(M - m0 < cap ? M - m0 : cap);
-        GemvBatch b;
-        b.count = 1;
-        b.out_f32 = out == HLQ_OUT_F32;
-        GemvProb &p = b.p[0];
-        p.packed = (const char *)packed;
-        p.x = X + (size_t)m0 * ldx;
-        p.y = (char *)Y + (size_t)m0 * ldy * ysz;
-        p.col_bytes = dm.col_bytes;
-        p.N = dm.N;
-        p.nchunks = dm.nchunks;
-        p.ntiles = dm.ntiles;
-        p.M = rows;
-        p.ldx = (long)ldx;
-        p.ldy = (long)ldy;
-        plan_mx_problem(dm, pl.W, pl.cpw, p);
-        p.blk_begin = 0;
-        p.cnt = (int *)ws;
-        p.part = (float *)((char *)ws + HLQ_WS_COUNTER_BYTES);
-        if (p.nslices > 1 && dm.ntiles > HLQ_WS_COUNTER_BYTES / 4) return HLQ_ERR_UNSUPPORTED;
-        for (int i = 1; i < HLQ_MAX_BATCH; ++i) b.p[i] = b.p[0];
-        const hlq_status s = hlq_launch_gemv_mx(b, (unsigned)((long)p.ntg * p.nslices), pl.W, rows <= rps ? 1 : 2, dm.q, dm.G, st);
-        if (s != HLQ_OK) return s;
-    }
-    return hlq_hip_status(hipGetLastError());
+    if (M < 1 || M > hlq_gemm_mx_rows_per_pass(dm.G)) return HLQ_ERR_UNSUPPORTED;
+    HlqGemvItem it;
+    it.dm = dm;
+    it.packed = packed;
+    it.x = X;
+    it.y = Y;
+    it.M = (int)M;
+    it.ldx = (long)ldx;
+    it.ldy = (long)ldy;
+    return hlq_launch_gemv_batch(1, &it, out, ws, st);
 }

@@ -87,6 +87,8 @@ struct HlqGemvItem {
     const void *packed;
     const uint16_t *x;
     void *y;
+    int M = 1;              // activation rows (all items of a launch carry the same number)
+    long ldx = 0, ldy = 0;  // row strides of x and y in elements (M > 1)
 };
 #define HLQ_MAX_BATCH 8
 hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws,
@@ -114,6 +116,7 @@ hlq_status hlq_launch_gemm_skinny(const HlqDims &dm, const void *packed, const u
                                   int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_gemm_path_override(int path);
 int hlq_gemm_mx_rows_per_pass(int G);
+bool hlq_gemm_uses_mx_rows(int64_t M);
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M);
 hlq_status hlq_launch_gemm_mx_rows(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
                                    void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);

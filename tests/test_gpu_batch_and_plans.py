@@ -94,3 +94,52 @@ def test_one_workspace_serves_different_shapes():
         torch.cuda.synchronize()
         ref = c_oracle.gemm_f64(x, codes, S, Z, q, G)
         assert O.row_rel_err(y.cpu().numpy().astype(np.float64)[None, :], ref).max() <= 2e-4   # default path
+
+
+@pytest.mark.parametrize("M,q,G", [(2, 4, 128), (4, 2, 128), (8, 4, 128), (3, 3, 64), (2, 2, 32), (16, 2, 128), (5, 2, 64)])
+def test_gemm_batch_equals_single_calls_and_oracle(M, q, G):
+    # M within one pass of the few-rows kernel -> one grouped launch; beyond it ((16, 128), (5, 64)) the
+    # problems run one after the other: results must be the same either way
+    shapes = [synth.Shape("a", 1024, 520), synth.Shape("b", 512, 64), synth.Shape("c", 4096, 200),
+              synth.Shape("d", 1024, 8)]
+    descs, packs, Xs, Ys, refs, singles = [], [], [], [], [], []
+    for s in shapes:
+        codes, S, Z = synth.make_weight(s.K, s.N, q, G, "gbatch", s.name)
+        X = synth.make_x(M, s.K, "gbatch", s.name, outliers=True)
+        d, p = pack_on_gpu(codes, S, Z, q, G)
+        descs.append(d); packs.append(p); Xs.append(dev(X))
+        Ys.append(torch.full((M, s.N), 7.0, dtype=torch.float32, device="cuda"))
+        refs.append(c_oracle.gemm_f64(X, codes, S, Z, q, G))
+        singles.append(B.hlq_lut_gemm(d, p, Xs[-1], out_f32=True))
+    batch = B.GemmBatch(descs, packs, Xs, Ys, out_f32=True)
+    for rep in range(2):                     # the workspace is reusable as is
+        batch.launch()
+        torch.cuda.synchronize()
+        for s, Y, ref, one in zip(shapes, Ys, refs, singles):
+            got = Y.cpu().numpy().astype(np.float64)
+            # the bar of the fp16-rebuild kernels that serve M > 8 (weights rounded to fp16; the
+            # 8-column problem normalises by the maximum over only 8 outputs)
+            assert O.row_rel_err(got, ref).max() <= TOL, s.name
+            assert O.row_rel_err(got, one.cpu().numpy().astype(np.float64)).max() <= TOL, s.name
+
+
+def test_gemm_batch_argument_errors():
+    import ctypes
+    d = B.make_desc(256, 64, 2, 128)
+    d3 = B.make_desc(256, 64, 3, 128)
+    ptrs = (ctypes.c_void_p * 2)(0x1000, 0x1000)
+    ld_ok = (ctypes.c_int64 * 2)(256, 256)
+    ldy_ok = (ctypes.c_int64 * 2)(64, 64)
+    ld_bad = (ctypes.c_int64 * 2)(256, 100)
+    ld_odd = (ctypes.c_int64 * 2)(260, 260)
+    mixed = (B.HlqDesc * 2)(d, d3)
+    same = (B.HlqDesc * 2)(d, d)
+    f = B.lib.hlq_lut_gemm_batch
+    assert f(2, mixed, ptrs, ptrs, 2, ld_ok, ptrs, ldy_ok, 0, 0x1000, 1 << 30, None) == 3      # mixed q
+    assert f(0, same, ptrs, ptrs, 2, ld_ok, ptrs, ldy_ok, 0, 0x1000, 1 << 30, None) == 3
+    assert f(9, same, ptrs, ptrs, 2, ld_ok, ptrs, ldy_ok, 0, 0x1000, 1 << 30, None) == 3
+    assert f(2, same, ptrs, ptrs, 2, ld_bad, ptrs, ldy_ok, 0, 0x1000, 1 << 30, None) == 5     # ldx < K
+    assert f(2, same, ptrs, ptrs, 2, ld_odd, ptrs, ldy_ok, 0, 0x1000, 1 << 30, None) == 5     # ldx % 8
+    assert f(2, same, ptrs, ptrs, 2, ld_ok, ptrs, ldy_ok, 0, 0x1000, 16, None) == 4           # workspace
+    assert f(2, same, None, ptrs, 2, ld_ok, ptrs, ldy_ok, 0, 0x1000, 1 << 30, None) == 1
+    assert f(2, same, ptrs, ptrs, 0, ld_ok, ptrs, ldy_ok, 0, 0x1000, 16, None) == 0           # M = 0: no-op
