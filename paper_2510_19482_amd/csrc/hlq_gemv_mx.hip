@@ -54,7 +54,7 @@
 #include "hlq_gemv_common.h"
 
 #ifndef HLQ_MX_DEBUG
-#define HLQ_MX_DEBUG 0   // timing experiments -- 1: loads only, 2: no reloads (compute only)
+#define HLQ_MX_DEBUG 0   // timing experiments -- 1: loads only (no MFMA work), 2: no reloads (compute only)
 #endif
 
 namespace {
@@ -131,13 +131,6 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     const int W = (int)(blockDim.x >> 6);
     extern __shared__ __attribute__((aligned(256))) char lds[];
 
-#if HLQ_MX_DEBUG == 9
-    long long ts[8];
-    ts[0] = wall_clock64();
-#define HLQ_TS(i) ts[i] = wall_clock64()
-#else
-#define HLQ_TS(i)
-#endif
     int pi = 0;
     for (int i = 1; i < b.count; ++i)
         if ((int)blockIdx.x >= b.p[i].blk_begin) pi = i;
@@ -195,8 +188,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         for (int sg = 0; sg < SEG; ++sg)
 #pragma unroll
             for (int r = 0; r <= Q; ++r)
-                if (HLQ_MX_DEBUG < 7 || HLQ_MX_DEBUG > 8) R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
-                else R.mt[sg][r] = 0;
+                R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
 #pragma unroll
         for (int m = 0; m < NROW; ++m)   // rows past M re-read the last row and are ignored
             R.x[m] = *(const uint32_t *)((const char *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)ch * 128) + xoff);
@@ -212,7 +204,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         const uint32_t *xr = (const uint32_t *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)cbeg * 128) + lane;
 #pragma unroll
         for (int i = 0; i < 8; ++i)
-            xu[m][i] = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0u : xr[(size_t)max(min(i, nrun - 1), 0) * 64];
+            xu[m][i] = xr[(size_t)max(min(i, nrun - 1), 0) * 64];
     }
 
     // weight loads of the first chunks (an empty run re-reads the slice's first chunk and drops it)
@@ -235,7 +227,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
             mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx),
                                                                         __builtin_bit_cast(ushort2_t, xu[m][i] & 0x7fff7fffu)));
         if (m < M)
-            for (int ci = 8; ci < ((HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0 : nrun); ++ci) {   // runs longer than eight chunks
+            for (int ci = 8; ci < nrun; ++ci) {   // runs longer than eight chunks
                 const uint32_t u = ((const uint32_t *)(P.x + (size_t)m * P.ldx + (size_t)(cbeg + ci) * 128))[lane] & 0x7fff7fffu;
                 mx = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mx), __builtin_bit_cast(ushort2_t, u)));
             }
@@ -246,7 +238,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         mx = max_dpp<0x128>(mx);         // row_ror:8: every lane holds its row's maximum
         mx = max_dpp<0x142, 0xa>(mx);    // row_bcast15: rows 1, 3 take rows 0, 2 in
         mx = max_dpp<0x143, 0xc>(mx);    // row_bcast31: row 3 takes row 1 in
-        const uint32_t top = (HLQ_MX_DEBUG >= 6 && HLQ_MX_DEBUG <= 8) ? 0x3c00u : (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
+        const uint32_t top = (uint32_t)__builtin_amdgcn_readlane((int)mx, 63);
         const int e = (int)(top >> 10);
         const int k1 = (29 - e) / 2, k2 = (29 - e) - k1 - (r_ == 0 ? 1 : r_ == 1 ? 2 : 3);   // -4 <= k2 <= 14
         const _Float16 f1 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k1) << 10));
@@ -255,7 +247,6 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         sw2[m] = (half2_t){f2, f2};
         yscale[m] = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + e) << 23);   // 4 * 2^(e-29)
     }
-    HLQ_TS(1);
 
     // ---- activation role: this lane converts x[2l], x[2l+1] of a chunk.  Weight k0 = 2 (l & 15) + h of
     // block g is plane bit (l & 15) + 16 h, i.e. register r = l & 3, nibble ((l >> 2) & 3) + 4 h of the
@@ -333,7 +324,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     // n-1; scheduling barriers keep the stages apart.  The LDS operands of the NEXT chunk are fetched
     // in the middle of the step.
     auto step = [&](Regs &R, const Pre &p, const Regs &Rn, Pre &pn, int ch_reload) {
-        if (HLQ_MX_DEBUG == 1 || (HLQ_MX_DEBUG >= 3 && HLQ_MX_DEBUG <= 8)) {   // timing experiment: loads only
+        if (HLQ_MX_DEBUG == 1) {   // timing experiment: loads only
             uint32_t m = 0;
 #pragma unroll
             for (int j = 0; j < Q; ++j) m ^= R.w[j][0] ^ R.w[j][1] ^ R.w[j][2] ^ R.w[j][3];
@@ -403,9 +394,8 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     };
 
     // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
-    HLQ_TS(2);
     Pre pre[2];
-    if (cbeg < cend && !(HLQ_MX_DEBUG == 1 || (HLQ_MX_DEBUG >= 3 && HLQ_MX_DEBUG <= 8))) prefetch(R[0], pre[0]);
+    if (cbeg < cend && HLQ_MX_DEBUG != 1) prefetch(R[0], pre[0]);
     for (int ch = cbeg; ch < cend; ch += NBUF) {
 #pragma unroll
         for (int i = 0; i < NBUF; ++i) {
@@ -413,23 +403,12 @@ hlq_gemv_mx_kernel(const GemvBatch b)
         }
     }
 
-    HLQ_TS(3);
     // ---- undo the run's scaling; add the four terms (lane groups) and the tile's KW runs ---------------------
 #pragma unroll
     for (int m = 0; m < NROW; ++m)
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) red[(m * 4 + cb) * 64 + lane] = acc[m][cb] * yscale[m];
-    if (HLQ_MX_DEBUG != 8) __syncthreads();
-    HLQ_TS(4);
-#if HLQ_MX_DEBUG == 9
-    if (lane == 0 && wave == 0) {
-        ts[5] = (long long)acc[0][0];
-        long long *dst = (long long *)((char *)b.p[0].cnt + 65536) + (size_t)(blockIdx.x % 1000) * 8;
-        for (int i = 0; i < 6; ++i) dst[i] = ts[i];
-        dst[6] = pi;
-        dst[7] = cend - cbeg;
-    }
-#endif
+    __syncthreads();
     if (part != 0 || !tile_ok) return;
     float y[NROW];
 #pragma unroll
@@ -443,7 +422,7 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     const size_t n = (size_t)tile * HLQ_TILE_N + lane;
     const size_t ldy = BATCHED ? (size_t)P.ldy : 0;
 
-    if (P.nslices == 1 || HLQ_MX_DEBUG == 5) {
+    if (P.nslices == 1) {
 #pragma unroll
         for (int m = 0; m < NROW; ++m)
             if (col_ok && m < M) store_out(P.y, m * ldy + n, y[m], b.out_f32);

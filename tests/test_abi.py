@@ -88,6 +88,43 @@ def test_host_side_argument_errors_launch_nothing():
     assert B.lib.hlq_lut_gemv(ctypes.byref(big), fake, fake, fake, 0, None, 0, None) == 1
 
 
+def test_workspace_sizes_cover_every_path():
+    # counters + room for split-K partial sums: K is never cut into slices shorter than four chunks,
+    # so (K/128 + 3) // 4 slices of N fp32 values bound every GEMV plan; a few-rows GEMM needs that
+    # per row; a grouped launch needs the sum over its problems
+    counters = 131072
+    t = ctypes.c_size_t()
+    for (K, N) in [(4096, 4096), (14336, 4096), (512, 64)]:
+        d = B.make_desc(K, N, 2, 128)
+        slices = (K // 128 + 3) // 4
+        gemv = slices * N * 4 if slices > 1 else 0
+        assert B.workspace_bytes(d, 1) >= counters + gemv
+        for M in (2, 4, 8):
+            assert B.workspace_bytes(d, M) >= counters + M * gemv
+        assert B.workspace_bytes(d, 8) <= B.workspace_bytes(d, 2048)
+    descs = [B.make_desc(4096, 4096, 2, 128), B.make_desc(14336, 4096, 2, 128)]
+    arr = (B.HlqDesc * 2)(*descs)
+    assert B.lib.hlq_gemm_batch_workspace_bytes(2, arr, 4, ctypes.byref(t)) == 0
+    single = [B.workspace_bytes(d, 4) - counters for d in descs]
+    assert t.value >= counters + sum(single) - 512
+    assert B.lib.hlq_gemm_batch_workspace_bytes(2, arr, 1, ctypes.byref(t)) == 0
+    assert t.value == B.batch_workspace_bytes(descs)
+    assert B.lib.hlq_gemm_batch_workspace_bytes(0, arr, 4, ctypes.byref(t)) == 3
+    assert B.lib.hlq_gemm_batch_workspace_bytes(2, arr, -1, ctypes.byref(t)) == 5
+    assert B.lib.hlq_gemm_batch_workspace_bytes(2, None, 4, ctypes.byref(t)) == 1
+
+
+def test_path_knobs_accept_documented_values_only():
+    for v in (0, 1, 2):
+        assert B.lib.hlq_set_gemv_path(v) == 0
+    for v in (0, 1, 2, 3):
+        assert B.lib.hlq_set_gemm_path(v) == 0
+    assert B.lib.hlq_set_gemv_path(3) == 3
+    assert B.lib.hlq_set_gemv_path(-1) == 3
+    assert B.lib.hlq_set_gemm_path(4) == 3
+    assert B.lib.hlq_set_gemv_path(0) == 0 and B.lib.hlq_set_gemm_path(0) == 0
+
+
 def test_status_strings():
     seen = set()
     for s in range(0, 7):
