@@ -108,6 +108,13 @@ def make_x(M: int, K: int, *key, outliers: bool = False) -> np.ndarray:
     return x.astype(np.float16)
 
 
+def make_dense_weight(K: int, N: int, *key, std: float = 0.02) -> np.ndarray:
+    """Unquantised weights W[K, N] fp32 ~ N(0, std): the bell shape the quantizer is designed for
+    (Sec. 3.1, Fig. 3)."""
+    rng = _rng("dense_weight", K, N, *key)
+    return rng.normal(0.0, std, size=(K, N)).astype(np.float32)
+
+
 def sample_columns(N: int, count: int, *key) -> np.ndarray:
     """Sorted sample of distinct column indices that always holds 0 and N-1."""
     count = min(count, N)
