@@ -84,6 +84,24 @@ HLQ_API hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, s
 /* Zero the arrival counters of a freshly allocated workspace (asynchronous on `stream`). */
 HLQ_API hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream);
 
+/* Alg. 1, Sec. 3.2 (alternating optimisation for HLQ): quantizes W[K, N] group by group (G
+ * consecutive k of a column) into the tensors hlq_pack consumes.  Start: uniform grid over the
+ * group's [min, max]; then t_max times (the paper uses 10): per weight the nearest of the 2^q
+ * values sum_j s_j bit_j(c) + z (ties: smallest code), then (s, z) by least squares given the
+ * bits.  fp64 arithmetic.  If the least-squares system of a group is rank deficient (a plane
+ * constant over the group, equal or complementary planes, all weights equal), columns are taken in
+ * the order 1, b_0, b_1, ... and a column that depends on the earlier ones keeps its previous
+ * parameter.  Plane j of the codes belongs to scale j (initially 2^j * Delta).
+ *   W         fp32 [K, N] row-major, finite
+ *   codes     u8   [K, N]      out; the codes chosen in the last iteration
+ *   scales    fp16 [q, K/G, N] out; zeros fp16 [K/G, N] out (rounded to nearest from fp64)
+ *   group_err fp32 [K/G, N]    out, may be NULL: squared reconstruction error of each group with
+ *                              the unrounded parameters (Eq. 7)
+ * 1 <= t_max <= 1000 and K/G <= 65535, else HLQ_ERR_UNSUPPORTED.  Integer codes and fp16
+ * parameters only: no workspace. */
+HLQ_API hlq_status hlq_quantize(const hlq_desc *d, const float *W, int t_max, uint8_t *codes,
+                                uint16_t *scales, uint16_t *zeros, float *group_err, void *stream);
+
 /* Offline step of App. B ("decomposed into q single-bit matrices offline") and of
  * App. D, Weight-Rearrange: split codes into bit-planes and store them so the runtime
  * kernel reads contiguous 128-bit words along the output-column dimension.

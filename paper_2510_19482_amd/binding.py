@@ -59,6 +59,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_batch_workspace_bytes.argtypes = [ctypes.c_int, dp, szp]
     lib.hlq_workspace_init.restype = ctypes.c_int
     lib.hlq_workspace_init.argtypes = [vp, sz, vp]
+    lib.hlq_quantize.restype = ctypes.c_int
+    lib.hlq_quantize.argtypes = [dp, vp, ctypes.c_int, vp, vp, vp, vp, vp]
     lib.hlq_gemm_batch_workspace_bytes.restype = ctypes.c_int
     lib.hlq_gemm_batch_workspace_bytes.argtypes = [ctypes.c_int, dp, ctypes.c_int64, szp]
     lib.hlq_lut_gemm_batch.restype = ctypes.c_int
@@ -184,6 +186,21 @@ def alloc_workspace(desc: HlqDesc, M: int, device="cuda", stream=None):
 
 def alloc_batch_workspace(descs, device="cuda", stream=None):
     return _new_workspace(batch_workspace_bytes(descs), device, stream)
+
+
+def hlq_quantize(desc: HlqDesc, W, t_max: int = 10, with_err: bool = False, stream=None):
+    """Alg. 1 on W fp32 cuda [K, N] -> codes u8 [K, N], scales fp16 [q, K/G, N], zeros fp16 [K/G, N]
+    (and the per-group squared error fp32 [K/G, N] with with_err=True)."""
+    import torch
+    assert W.dtype == torch.float32 and W.is_contiguous() and tuple(W.shape) == (desc.K, desc.N)
+    dev = W.device
+    codes = torch.empty((desc.K, desc.N), dtype=torch.uint8, device=dev)
+    scales = torch.empty((desc.q, desc.K // desc.G, desc.N), dtype=torch.float16, device=dev)
+    zeros = torch.empty((desc.K // desc.G, desc.N), dtype=torch.float16, device=dev)
+    err = torch.empty((desc.K // desc.G, desc.N), dtype=torch.float32, device=dev) if with_err else None
+    _check("hlq_quantize", lib.hlq_quantize(ctypes.byref(desc), _ptr(W), t_max, _ptr(codes), _ptr(scales), _ptr(zeros),
+                                            _ptr(err) if with_err else None, _stream_ptr(stream)))
+    return (codes, scales, zeros, err) if with_err else (codes, scales, zeros)
 
 
 class GemvBatch:

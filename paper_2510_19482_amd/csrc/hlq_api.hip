@@ -141,6 +141,19 @@ hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint16_t *sca
     return hlq_launch_pack(dm, codes, scales, zeros, packed, (hipStream_t)stream);
 }
 
+hlq_status hlq_quantize(const hlq_desc *d, const float *W, int t_max, uint8_t *codes, uint16_t *scales,
+                        uint16_t *zeros, float *group_err, void *stream)
+{
+    HlqDims dm;
+    hlq_status s = hlq_check_desc(d, &dm);
+    if (s != HLQ_OK) return s;
+    if (!W || !codes || !scales || !zeros) return HLQ_ERR_NULL;
+    if (t_max < 1 || t_max > 1000) return HLQ_ERR_UNSUPPORTED;
+    if (misaligned(W, 4) || misaligned(scales, 2) || misaligned(zeros, 2) || (group_err && misaligned(group_err, 4)))
+        return HLQ_ERR_BAD_STRIDE;
+    return hlq_launch_quantize(dm, W, t_max, codes, scales, zeros, group_err, (hipStream_t)stream);
+}
+
 hlq_status hlq_unpack(const hlq_desc *d, const void *packed, uint8_t *codes, uint16_t *scales,
                       uint16_t *zeros, void *stream)
 {

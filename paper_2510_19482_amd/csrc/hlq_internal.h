@@ -81,6 +81,9 @@ hlq_status hlq_launch_pack(const HlqDims &dm, const uint8_t *codes, const uint16
 hlq_status hlq_launch_unpack(const HlqDims &dm, const void *packed, uint8_t *codes,
                              uint16_t *scales, uint16_t *zeros, hipStream_t st);
 
+hlq_status hlq_launch_quantize(const HlqDims &dm, const float *W, int t_max, uint8_t *codes, uint16_t *scales,
+                               uint16_t *zeros, float *group_err, hipStream_t st);
+
 // One GEMV of a grouped launch (all problems of a launch share q and G).
 struct HlqGemvItem {
     HlqDims dm;
