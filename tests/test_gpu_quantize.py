@@ -78,6 +78,27 @@ def test_degenerate_groups_follow_the_rank_rule():
     assert half_ulps(S, S_ref.astype(np.float16)).max() <= 1 and half_ulps(Z, Z_ref.astype(np.float16)).max() <= 1
 
 
+@pytest.mark.parametrize("q,G", [(1, 32), (3, 32), (4, 32), (3, 128), (4, 128), (4, 256)])
+def test_groups_with_few_distinct_values(q, G):
+    # groups holding only 1..6 distinct values leave most codes unused, so the least-squares system
+    # is rank deficient in many different ways (constant planes, equal planes, complementary planes)
+    K, N = max(2 * G, 128), 48
+    rng = np.random.default_rng(1000 * q + G)
+    W = np.empty((K, N), dtype=np.float32)
+    for n in range(N):
+        for g in range(K // G):
+            nd = 1 + (n + g) % 6
+            vals = (rng.standard_normal(nd) * 0.02).astype(np.float32)
+            W[g * G:(g + 1) * G, n] = vals[rng.integers(0, nd, G)]
+    codes_ref, S_ref, Z_ref = QO.quantize(W.astype(np.float64), q, G, t_max=10)
+    _, (codes, S, Z, err) = run_gpu(W, q, G, 10, with_err=True)
+    assert np.all(np.isfinite(S.astype(np.float32))) and np.all(np.isfinite(Z.astype(np.float32)))
+    assert np.array_equal(codes, codes_ref)
+    assert half_ulps(S, S_ref.astype(np.float16)).max() <= 1 and half_ulps(Z, Z_ref.astype(np.float16)).max() <= 1
+    err_ref = ((QO.reconstruct(codes_ref, S_ref, Z_ref, q, G) - W.astype(np.float64)) ** 2).reshape(K // G, G, N).sum(axis=1)
+    assert np.allclose(err, err_ref, rtol=1e-5, atol=1e-12)
+
+
 def test_beats_round_to_nearest_at_size():
     # a whole 8B-shaped projection matrix: properties that hold at any size (Fig. 3's claim; never
     # worse than the uniform grid it starts from), plus sampled groups against the oracle
