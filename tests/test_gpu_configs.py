@@ -68,3 +68,11 @@ def test_config5_70b_layer_decode(shape, G):
 
 def test_config5_lm_head():
     check(synth.LLAMA31_70B_LM_HEAD, 2, 128, 1, "cfg5", False, ncols=512)
+
+
+@pytest.mark.parametrize("shape", [synth.Shape("qkv_fused", 4096, 6144), synth.Shape("gate_up_fused", 4096, 28672)],
+                         ids=lambda s: s.name)
+def test_fused_decode_shapes(shape):
+    # the fused projections of the decode loop bench.py times (q|k|v as one N = 6144 GEMV, gate|up as
+    # one N = 28672 GEMV); sampled columns for the wide one
+    check(shape, 2, 128, 1, "fused", False, ncols=None if shape.N <= 8192 else 2048)
