@@ -75,7 +75,9 @@ HLQ_API hlq_status hlq_packed_bytes(const hlq_desc *d, size_t *total, size_t *bi
  * The workspace holds split-K arrival counters and partial sums.  It must be passed once
  * through hlq_workspace_init after allocation; every call leaves it initialised, so one
  * workspace can serve any number of successive calls (also of different shapes, if large
- * enough for each).  Two calls that may run concurrently need separate workspaces. */
+ * enough for each).  Two calls that may run concurrently need separate workspaces.
+ * The size is that of a call with exactly M rows and is not monotone in M (the split of K is
+ * planned per M): a workspace meant for several M must cover the largest of their sizes. */
 HLQ_API hlq_status hlq_workspace_bytes(const hlq_desc *d, int64_t M, size_t *bytes);
 
 /* Workspace size for hlq_lut_gemv_batch over `count` descriptors (host array). */

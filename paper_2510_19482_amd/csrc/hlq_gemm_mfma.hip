@@ -10,7 +10,12 @@
 // Work split.  A workgroup (4 wavefronts) owns 32*MW rows x 256 columns x a K slice; wavefront w
 // owns column tile 4*blockIdx.x + w (lane <-> column, the same records the GEMV reads) and keeps
 // MW x 2 accumulator tiles of 32x32.  The X tile of the current chunk (32*MW rows x 128 k) is
-// staged in LDS once per workgroup, double-buffered, one barrier per chunk.
+// staged in LDS once per workgroup, double-buffered, one barrier per chunk.  It gets there by
+// global_load_lds_dwordx4: memory -> LDS without passing through registers, 16 bytes per lane,
+// lane L of an instruction landing at (base in M0) + 16 L.  A staged row is 16 such units with no
+// padding; unit u of row r sits at position u ^ (r & 7), which spreads the eight rows that one
+// 128-bit fragment read touches per cycle over all banks.  Each lane picks the global address
+// whose data belongs at its LDS position, so one instruction still reads four whole 256-byte rows.
 //
 // Rebuilding weights.  A lane holds, per plane, the 128 bits of its column for the chunk; in a
 // 32-bit plane word bits p and p+16 are the adjacent weights k0 = 2p, 2p+1 of the word's 32-k
@@ -39,14 +44,26 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
     else ((_Float16 *)y)[idx] = (_Float16)v;   // round-to-nearest-even
 }
 
-constexpr int XROW = 128 + 8;   // halfs per staged X row: 128 k + 16 bytes of padding (bank spread)
+constexpr int XROW = 128;   // halfs per staged X row: the 128 k of a chunk as 16 swizzled 16-byte units
+
+// vmcnt(0) with the other counters left alone (expcnt 7, lgkmcnt 15)
+constexpr int WAIT_VM0 = (7 << 4) | (15 << 8);
+
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane.  Issued as inline
+// assembly so that the compiler's wait-count bookkeeping does not tie later LDS reads (of the other
+// buffer) to it; completion is awaited explicitly (vmcnt) before the barrier that publishes the tile.
+__device__ __forceinline__ void dma_16B_per_lane(const void *gptr, uint32_t lds_base)
+{
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory", "m0");
+}
 
 template <int Q, int G>
 struct WRegs {
     static constexpr int GS = G < 128 ? G : 128;
     static constexpr int SEG = 128 / GS;
     uint32_t w[Q][4];
-    uint16_t mt[SEG][Q + 1];
+    uint32_t mt[SEG][Q + 1];   // fp16 bit patterns, one register each: a 16-bit load then needs no merge (and
+                               // no wait for the load) before its first real use
 };
 
 template <int Q, int G, int MW>
@@ -91,32 +108,25 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
             for (int r = 0; r <= Q; ++r) R.mt[sg][r] = m[(sg * (Q + 1) + r) * tw + lane_c];
     };
 
-    // X staging: item (row, 32-k block d) = 64 contiguous bytes of X, copied to LDS as they are.
-    // ROWS*4 items, 256 lanes.
-    constexpr int ITEMS = (ROWS * 4 + 255) / 256;
-    uint4 xreg[ITEMS][4];
-    auto load_x = [&](int c) {
+    // X staging: wavefront w fills rows [w ROWS/4, (w+1) ROWS/4) of the tile, four rows per instruction;
+    // lane L writes position L & 15 of row 4 i + (L >> 4), i.e. it fetches unit (L & 15) ^ (row & 7).
+    // Rows past M re-read row M - 1: they only feed accumulator rows that are never stored.
+    constexpr int RPW = ROWS / 4, NDMA = RPW / 4;
+    const _Float16 *xsrc[NDMA];
 #pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const int item = tid + it * 256;
-            const int row = item >> 2, d = item & 3;
-            const int m = m0 + row;
-            const bool ok = item < ROWS * 4 && m < M;
-            const uint4 *src = (const uint4 *)(X + (size_t)(ok ? m : 0) * ldx + (size_t)c * 128 + d * 32);
+    for (int i = 0; i < NDMA; ++i) {
+        const int row = wave * RPW + 4 * i + (lane >> 4);
+        const int u = (lane & 15) ^ (row & 7);
+        const int m = min(m0 + row, M - 1);
+        xsrc[i] = (const _Float16 *)X + (size_t)m * ldx + u * 8;
+    }
+    // LDS byte address of this wavefront's rows in buffer 0 (wave-uniform: it goes to M0)
+    const uint32_t lds_wave = (uint32_t)__builtin_amdgcn_readfirstlane(
+        (int)(uint32_t)(uintptr_t)(__attribute__((address_space(3))) _Float16 *)(Xs + (size_t)wave * RPW * XROW));
+    auto dma_x = [&](int c, int buf) {
 #pragma unroll
-            for (int v = 0; v < 4; ++v) xreg[it][v] = ok ? src[v] : make_uint4(0u, 0u, 0u, 0u);
-        }
-    };
-    auto store_x = [&](int buf) {
-#pragma unroll
-        for (int it = 0; it < ITEMS; ++it) {
-            const int item = tid + it * 256;
-            if (item >= ROWS * 4) continue;
-            const int row = item >> 2, d = item & 3;
-            uint4 *dst = (uint4 *)(Xs + ((size_t)buf * ROWS + row) * XROW + d * 32);
-#pragma unroll
-            for (int v = 0; v < 4; ++v) dst[v] = xreg[it][v];
-        }
+        for (int i = 0; i < NDMA; ++i)
+            dma_16B_per_lane(xsrc[i] + (size_t)c * 128, lds_wave + (uint32_t)((buf * ROWS + 4 * i) * XROW * 2));
     };
 
     float16v acc[MW][2];
@@ -127,7 +137,11 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mb][cb][r] = 0.f;
 
-    const _Float16 *xrow = Xs + (size_t)(lane & 31) * XROW + (lane >> 5) * 8;   // this lane's A-fragment origin
+    // A fragments: lane l reads row l & 31 of a row block, logical unit 4 d + 2 ks + (l >> 5), stored at
+    // that number ^ (l & 7): four per-lane origins cover the low bits, bit 3 is an immediate offset
+    const _Float16 *xrow[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) xrow[k] = Xs + (size_t)(lane & 31) * XROW + (((2 * k) | (lane >> 5)) ^ (lane & 7)) * 8;
 
     // One chunk = 8 MW steps; step s = ((word d, k-step ks), row block mb) issues the two MFMAs of row
     // block mb against the two 32-column halves of the tile.  The wavefront issues in order and an
@@ -138,11 +152,11 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
     //   - the four lane exchanges that form the B operands of the next k-step are spread over the MW
     //     steps of the current one.
     auto compute = [&](const Regs &R, int buf) {
-        const _Float16 *xb = xrow + (size_t)buf * ROWS * XROW;
+        const size_t xb = (size_t)buf * ROWS * XROW;
         constexpr int STEPS = 8 * MW, SPW = 2 * MW, PPS = 16 / SPW, XPS = (4 + MW - 1) / MW;
         auto frag = [&](int s) -> half8v {
             const int mb = s % MW, ks = (s / MW) & 1, d = s / SPW;
-            return *(const half8v *)(xb + (size_t)mb * 32 * XROW + d * 32 + ks * 16);
+            return *(const half8v *)(xrow[(d & 1) * 2 + ks] + xb + (size_t)mb * 32 * XROW + (d >> 1) * 64);
         };
         uint32_t wp[2][16];   // rebuilt pairs of the current / next word: wp[d & 1][p] = k 32d + 2p, 2p + 1
         HlqSegScales<Q> sc;
@@ -196,25 +210,32 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
         }
     };
 
-    // ---- chunk loop: X double-buffered in LDS, weights of chunk c+1 and X of chunk c+1 prefetched ----
+    // ---- chunk loop: weights (registers) and X (LDS) of chunk c + 2 are requested right after the barrier
+    //      that ends chunk c and have the whole of chunk c + 1 to arrive ------------------------------------
     if (cbeg < cend) {
         Regs RA, RB;
         load_w(cbeg, RA);
-        load_x(cbeg);
-        store_x(0);
         load_w(min(cbeg + 1, cend - 1), RB);
+        dma_x(cbeg, 0);
+        if (cbeg + 1 < cend) dma_x(cbeg + 1, 1);
+        __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+        __syncthreads();
         for (int c = cbeg; c < cend; c += 2) {
-            __syncthreads();
-            if (c + 1 < cend) load_x(c + 1);
             compute(RA, 0);
-            load_w(min(c + 2, cend - 1), RA);
+            __builtin_amdgcn_s_waitcnt(WAIT_VM0);   // own share of chunk c + 1 has landed
+            __syncthreads();                        // everyone's has; buffer 0 is free
+            if (c + 2 < cend) {
+                load_w(c + 2, RA);
+                dma_x(c + 2, 0);
+            }
             if (c + 1 < cend) {
-                store_x(1);
-                __syncthreads();
-                if (c + 2 < cend) load_x(c + 2);
                 compute(RB, 1);
-                load_w(min(c + 3, cend - 1), RB);
-                if (c + 2 < cend) store_x(0);
+                __builtin_amdgcn_s_waitcnt(WAIT_VM0);
+                __syncthreads();
+                if (c + 3 < cend) {
+                    load_w(c + 3, RB);
+                    dma_x(c + 3, 1);
+                }
             }
         }
     }
@@ -264,6 +285,11 @@ struct MfmaPlan {
     int MW, cps, nslices, rowblocks;
 };
 
+// K split.  A workgroup takes cps chunks; nslices = ceil(nchunks / cps) slices leave fp32 partials that
+// a second kernel adds.  The choice minimises a small cost model fitted to measurements on MI355X
+// (M = 512 / 2048, the 8B layer shapes): a chunk costs a workgroup t1 when it has its CU to itself
+// and t2 = 1.65 t1 when two workgroups share the CU (two per CU is the occupancy limit), workgroups
+// run in rounds of 512, and the reduction costs a launch plus reading the partials back.
 MfmaPlan plan_mfma(const HlqDims &dm, int64_t M)
 {
     MfmaPlan p;
@@ -271,14 +297,25 @@ MfmaPlan plan_mfma(const HlqDims &dm, int64_t M)
     p.rowblocks = (int)((M + 32 * p.MW - 1) / (32 * p.MW));
     const long colgroups = (dm.ntiles + 3) / 4;
     const long wgs = colgroups * p.rowblocks;
-    long want = (512 + wgs - 1) / wgs;                   // K slices wanted to cover the CUs twice
-    const long max_slices = (dm.nchunks + 3) / 4;        // at least 4 chunks per slice
-    if (want > max_slices) want = max_slices;
-    if (want < 1) want = 1;
-    int cps = (int)((dm.nchunks + want - 1) / want);
-    cps = (cps + 1) & ~1;
-    p.cps = cps;
-    p.nslices = (dm.nchunks + cps - 1) / cps;
+    const double t1 = 0.64 * p.MW * (1.0 + 0.1 * (dm.q - 2)), t2 = 1.65 * t1;   // us per chunk and workgroup
+    const double mn = (double)M * (double)dm.N;
+    double best = 0.0;
+    const int top = (dm.nchunks + 1) & ~1;   // cps is even: the chunk loop alternates two register sets
+    p.cps = top;
+    p.nslices = 1;
+    for (int cps = top;; cps -= 2) {
+        const int ns = (dm.nchunks + cps - 1) / cps;
+        const long total = wgs * ns;
+        const long full = total / 512, rem = total % 512;
+        double t = cps * (full * t2 + (rem == 0 ? 0.0 : (rem <= 256 ? t1 : t2)));
+        if (ns > 1) t += 5.0 + ns * mn * 4.0 / 4.0e6;
+        if (best == 0.0 || t < best) {
+            best = t;
+            p.cps = cps;
+            p.nslices = ns;
+        }
+        if (cps - 2 < 4) break;   // at least four chunks per slice
+    }
     return p;
 }
 

@@ -22,13 +22,15 @@ __host__ __device__ constexpr int hlq_pair_shift(int p) { return p == 15 ? -1 : 
 template <int Q>
 struct HlqSegScales {
     half2v z2, s13[Q], s14[Q];
-    __device__ __forceinline__ void set(const uint16_t (&mt)[Q + 1])
+    // mt: fp16 bit patterns of s_0 .. s_{Q-1}, z (16- or 32-bit containers)
+    template <typename T>
+    __device__ __forceinline__ void set(const T (&mt)[Q + 1])
     {
-        const _Float16 z = __builtin_bit_cast(_Float16, mt[Q]);
+        const _Float16 z = __builtin_bit_cast(_Float16, (uint16_t)mt[Q]);
         z2 = (half2v){z, z};
 #pragma unroll
         for (int j = 0; j < Q; ++j) {
-            const _Float16 s = __builtin_bit_cast(_Float16, mt[j]);
+            const _Float16 s = __builtin_bit_cast(_Float16, (uint16_t)mt[j]);
             const _Float16 a = s * (_Float16)128.0f, b = s * (_Float16)0.5f;
             s13[j] = (half2v){a, a};
             s14[j] = (half2v){b, b};
