@@ -170,11 +170,12 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
 /* Tuning knob (process-wide, not thread-safe): formulation used by hlq_lut_gemm for M > 1.
  * 0 = automatic (matrix cores from M = 2 on, the measured crossover),
  * 1 = table lookups always,
- * 2 = matrix cores always: for a few rows (M <= 8 at G >= 128, <= 4 at G = 64, <= 2 at G = 32) the
+ * 2 = matrix cores always: for a few rows (M <= 4 at G >= 128, <= 2 at G = 64, 1 at G = 32) the
  *     GEMV kernel of hlq_set_gemv_path(2) with several activation rows per operand, above that
- *     kernels that rebuild W^ in fp16 registers (M <= 32 streaming, larger M tiled),
+ *     the tiled kernel that rebuilds W^ in fp16 registers (hlq_lut_gemm_batch keeps up to twice
+ *     as many rows on the GEMV kernel, where one launch for several problems pays),
  * 3 = as 2 but never the few-rows GEMV kernel.
- * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernels require |s_j| < 512. */
+ * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel requires |s_j| < 512. */
 HLQ_API hlq_status hlq_set_gemm_path(int path);
 
 /* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded

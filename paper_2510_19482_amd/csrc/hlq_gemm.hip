@@ -273,10 +273,9 @@ bool hlq_gemm_uses_mx_rows(int64_t M) { return use_mfma(M) && g_gemm_path != 3; 
 size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
 {
     size_t a = hlq_gemm_lut_partial_bytes(dm, M);
-    const size_t b = hlq_gemm_mfma_partial_bytes(dm, M), c = hlq_gemm_skinny_partial_bytes(dm, M);
+    const size_t b = hlq_gemm_mfma_partial_bytes(dm, M);
     const size_t e = hlq_gemm_mx_partial_bytes(dm, M);
     if (b > a) a = b;
-    if (c > a) a = c;
     if (e > a) a = e;
     return a;
 }
@@ -285,12 +284,11 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
                            void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st)
 {
     if (use_mfma(M)) {
-        // as many rows as one pass of the matrix-core GEMV kernel carries (several activation rows per
-        // operand; measured faster than the fp16 streaming kernel up to there, slower with two passes);
-        // then the GEMV-shaped fp16 kernel; many rows: tiled kernel with X staged in LDS
-        if (g_gemm_path != 3 && M <= hlq_gemm_mx_rows_per_pass(dm.G))
+        // up to one row set of the matrix-core GEMV kernel (several activation rows per operand): measured
+        // faster than the tiled kernel there; from the second row set on the tiled kernel, whose time
+        // hardly depends on M up to 32 rows, is as fast or faster for a single call
+        if (g_gemm_path != 3 && M <= hlq_gemv_mx_rows_per_set(dm.G))
             return hlq_launch_gemm_mx_rows(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
-        if (M <= 32) return hlq_launch_gemm_skinny(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
         return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
     }
     return hlq_launch_gemm_lut(dm, packed, X, M, ldx, Y, ldy, out, ws, st);

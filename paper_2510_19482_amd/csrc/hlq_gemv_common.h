@@ -37,4 +37,3 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
 // per tile: ntg = ceil(ntiles / (W / kw)) tile groups, one arrival counter per TILE
 hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int q, int G, hipStream_t st);
 int hlq_gemv_mx_max_waves(int q, int G);
-int hlq_gemv_mx_rows_per_set(int G);

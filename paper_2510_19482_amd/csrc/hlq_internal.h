@@ -114,10 +114,8 @@ hlq_status hlq_launch_gemm_lut(const HlqDims &dm, const void *packed, const uint
                                int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
                                 int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
-size_t hlq_gemm_skinny_partial_bytes(const HlqDims &dm, int64_t M);
-hlq_status hlq_launch_gemm_skinny(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
-                                  int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_gemm_path_override(int path);
+int hlq_gemv_mx_rows_per_set(int G);
 int hlq_gemm_mx_rows_per_pass(int G);
 bool hlq_gemm_uses_mx_rows(int64_t M);
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M);

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True, params=["matrix-core", "fp16-rebuild-only"])
 def mfma_path(request):
     # "matrix-core" sends a few rows to the GEMV kernel with several activation rows per operand,
-    # "fp16-rebuild-only" keeps them on the fp16 streaming kernel; larger M is the same in both
+    # "fp16-rebuild-only" keeps them on the tiled fp16 kernel; larger M is the same in both
     B.set_gemm_path(B.GEMM_MFMA if request.param == "matrix-core" else B.GEMM_MFMA_FP16)
     yield
     B.set_gemm_path(B.GEMM_AUTO)
@@ -79,10 +79,10 @@ def test_mfma_identity_rows_read_back_weights():
 
 @pytest.mark.parametrize("M", [3, 16, 29])
 def test_few_rows_one_hot_read_back_weights(M):
-    # one-hot rows through the few-row kernel (M <= 32): checks its lane-group transpose, A-fragment
-    # addressing and output layout entry by entry
+    # one-hot rows, fewer than one 32-row tile: checks the lane exchange, the A-fragment addressing
+    # (swizzled LDS rows, rows past M) and the output layout entry by entry
     K, N, q, G = 512, 200, 3, 64
-    codes, S, Z = synth.make_weight(K, N, q, G, "skinny-id")
+    codes, S, Z = synth.make_weight(K, N, q, G, "one-hot-rows")
     d, packed = pack_on_gpu(codes, S, Z, q, G)
     W = O.dequantize(codes, S, Z, q, G)
     ks = (np.arange(M) * 37 + 5) % K
