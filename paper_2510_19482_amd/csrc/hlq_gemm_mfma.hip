@@ -287,7 +287,7 @@ struct MfmaPlan {
 
 // K split.  A workgroup takes cps chunks; nslices = ceil(nchunks / cps) slices leave fp32 partials that
 // a second kernel adds.  The choice minimises a small cost model fitted to measurements on MI355X
-// (M = 512 / 2048, the 8B layer shapes): a chunk costs a workgroup t1 when it has its CU to itself
+// (M = 16 .. 2048, the 8B layer shapes): a chunk costs a workgroup t1 when it has its CU to itself
 // and t2 = 1.65 t1 when two workgroups share the CU (two per CU is the occupancy limit), workgroups
 // run in rounds of 512, and the reduction costs a launch plus reading the partials back.
 MfmaPlan plan_mfma(const HlqDims &dm, int64_t M)
@@ -297,7 +297,8 @@ MfmaPlan plan_mfma(const HlqDims &dm, int64_t M)
     p.rowblocks = (int)((M + 32 * p.MW - 1) / (32 * p.MW));
     const long colgroups = (dm.ntiles + 3) / 4;
     const long wgs = colgroups * p.rowblocks;
-    const double t1 = 0.64 * p.MW * (1.0 + 0.1 * (dm.q - 2)), t2 = 1.65 * t1;   // us per chunk and workgroup
+    // us per chunk and workgroup: rebuilding the weights (per plane) + MFMAs and fragment reads (per row block)
+    const double t1 = 0.275 * dm.q + 0.5 * p.MW, t2 = 1.65 * t1;
     const double mn = (double)M * (double)dm.N;
     double best = 0.0;
     const int top = (dm.nchunks + 1) & ~1;   // cps is even: the chunk loop alternates two register sets
@@ -314,7 +315,7 @@ MfmaPlan plan_mfma(const HlqDims &dm, int64_t M)
             p.cps = cps;
             p.nslices = ns;
         }
-        if (cps - 2 < 4) break;   // at least four chunks per slice
+        if (cps - 2 < 2) break;
     }
     return p;
 }
