@@ -145,7 +145,9 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
 
     // One chunk = 8 MW steps; step s = ((word d, k-step ks), row block mb) issues the two MFMAs of row
     // block mb against the two 32-column halves of the tile.  The wavefront issues in order and an
-    // MFMA takes 64 cycles, so everything else is spread between the MFMAs as side work of a step,
+    // MFMA occupies the matrix core for 32 cycles (and the vector issue port for about 8; up to six
+    // plain vector instructions per MFMA issue for free), so everything else is spread between the
+    // MFMAs as side work of a step,
     // one stage ahead of its use (scheduling barriers keep the stages apart):
     //   - the A fragment of step s + 1 (one 128-bit LDS read) is requested before the MFMAs of step s;
     //   - the 16 weight pairs of word d + 1 are rebuilt 16 / (2 MW) per step during word d;
