@@ -200,12 +200,9 @@ hlq_gemv_kernel(const GemvBatch b)
     float *red = lds + W * (HLQ_GEMV_TABLE_BYTES / 4);
 
     // ---- which problem, which column tile group, which K slice ---------------------------------
-    int pi = 0;
-    for (int i = 1; i < b.count; ++i)
-        if ((int)blockIdx.x >= b.p[i].blk_begin) pi = i;
-    const GemvProb &P = b.p[pi];
-    const int local = (int)blockIdx.x - P.blk_begin;
-    const int tg = local / P.nslices, slice = local % P.nslices;
+    const GemvProb P = b.p[gemv_problem_of(b, (int)blockIdx.x)];   // a copy: one burst of scalar loads
+    int tg, slice;
+    gemv_split_block(P, (int)blockIdx.x - P.blk_begin, tg, slice);
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -596,7 +593,13 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
             p.nslices = slices_for(dm, cps);
             p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
         }
+        p.kw_shift = 0;
+        while ((1 << p.kw_shift) < p.kw) ++p.kw_shift;
+        // exact for local * nslices < 2^32, far above any grid this library launches (checked below)
+        p.slice_magic = p.nslices > 1 ? (unsigned)((0x100000000ULL + (unsigned)p.nslices - 1) / (unsigned)p.nslices) : 0u;
+        if ((unsigned long long)p.ntg * p.nslices * p.nslices >= 0x100000000ULL) return HLQ_ERR_UNSUPPORTED;
         p.blk_begin = (int)blk;
+        b.blk_begin[i] = (int)blk;
         p.cnt = cnt + cnt_used;
         p.part = part;
         blk += (long)p.ntg * p.nslices;
@@ -605,7 +608,10 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
             part += (size_t)p.nslices * dm.N * rows;
         }
     }
-    for (int i = count; i < HLQ_MAX_BATCH; ++i) b.p[i] = b.p[0];
+    for (int i = count; i < HLQ_MAX_BATCH; ++i) {
+        b.p[i] = b.p[0];
+        b.blk_begin[i] = 0x7fffffff;
+    }
     if (cnt_used > HLQ_WS_COUNTER_BYTES / 4 || blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
 
     const int q = items[0].dm.q, G = items[0].dm.G;

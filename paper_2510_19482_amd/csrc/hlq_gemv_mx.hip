@@ -131,25 +131,22 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     const int W = (int)(blockDim.x >> 6);
     extern __shared__ __attribute__((aligned(256))) char lds[];
 
-    int pi = 0;
-    for (int i = 1; i < b.count; ++i)
-        if ((int)blockIdx.x >= b.p[i].blk_begin) pi = i;
-    const GemvProb &P = b.p[pi];
-    const int local = (int)blockIdx.x - P.blk_begin;
-    const int tg = local / P.nslices, slice = local % P.nslices;
+    const GemvProb P = b.p[gemv_problem_of(b, (int)blockIdx.x)];   // a copy: one burst of scalar loads
+    int tg, slice;
+    gemv_split_block(P, (int)blockIdx.x - P.blk_begin, tg, slice);
 
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int KW = P.kw, part = wave % KW;
-    const int tile = tg * (W / KW) + wave / KW;
+    const int KW = P.kw, KSH = P.kw_shift, part = wave & (KW - 1);   // W and KW are powers of two
+    const int tile = tg * (W >> KSH) + (wave >> KSH);
     const bool tile_ok = tile < P.ntiles;               // a surplus wavefront gets an empty run
     const int tile_c = tile_ok ? tile : P.ntiles - 1;
     // this wavefront's run of chunks: the slice is cut into KW near-equal parts
     const int sbeg = slice * P.cps;
     const int send = min(sbeg + P.cps, P.nchunks);
     const int len = send - sbeg;
-    const int cbeg = sbeg + (len * part) / KW;
-    const int cend = tile_ok ? sbeg + (len * (part + 1)) / KW : cbeg;
+    const int cbeg = sbeg + ((len * part) >> KSH);
+    const int cend = tile_ok ? sbeg + ((len * (part + 1)) >> KSH) : cbeg;
 
     const int tw = hlq_tile_width(tile_c, P.N);
     const char *tile_base = P.packed + (size_t)tile_c * HLQ_TILE_N * P.col_bytes;
@@ -164,8 +161,6 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     float *red = (float *)(meta + 64 * MSTR);         // [row][4][64]
     constexpr int RSTR = PERW / 4;                    // floats between wavefronts' sums
     const int M = BATCHED ? P.M : 1;
-    // rows past M are never converted: their codes stay zero
-    for (int i = lane; i < mx_xt_bytes(NROW) / 4; i += 64) ((uint32_t *)xt)[i] = 0u;
 
     auto load_chunk = [&](int ch, Regs &R) {
         // The lane offsets pass through an empty asm: they are re-extended to 64 bits at each use,
@@ -211,6 +206,10 @@ hlq_gemv_mx_kernel(const GemvBatch b)
     Regs R[NBUF];
 #pragma unroll
     for (int i = 0; i < NBUF; ++i) load_chunk(max(min(cbeg + i, cend - 1), sbeg), R[i]);
+
+    // with the first loads on their way: clear the operand area (rows past M are never converted, their
+    // codes stay zero)
+    for (int i = lane; i < mx_xt_bytes(NROW) / 4; i += 64) ((uint32_t *)xt)[i] = 0u;
 
     // per activation row: largest magnitude -> power-of-two scale.  Biased fp16 exponent e of the largest
     // magnitude: |x| < 2^(e-14); scaling by 2^(29-e) gives |x| < 2^15.  Plane codes are worth 1/2, 1, 2, 2
