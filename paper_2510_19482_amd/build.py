@@ -17,6 +17,9 @@ FLAGS = [
     "-Wno-unused-command-line-argument",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
+# per-file additions.  The matrix-core GEMV kernel takes the table of first blocks and the flags as its
+# first ten scalar arguments and has them preloaded into scalar registers at wavefront start.
+EXTRA_FLAGS = {"hlq_gemv_mx.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"]}
 
 
 def build(verbose: bool = False) -> str:
@@ -25,7 +28,7 @@ def build(verbose: bool = False) -> str:
     procs = []
     for src in SOURCES:
         obj = os.path.join(CSRC, src.replace(".hip", ".o"))
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *EXTRA_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
