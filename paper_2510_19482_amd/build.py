@@ -19,7 +19,9 @@ FLAGS = [
 ]
 # per-file additions.  The matrix-core GEMV kernel takes the table of first blocks and the flags as its
 # first ten scalar arguments and has them preloaded into scalar registers at wavefront start.
-EXTRA_FLAGS = {"hlq_gemv_mx.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"]}
+# The tiled GEMM kernel gets its leading arguments (pointers, strides, M) the same way.
+EXTRA_FLAGS = {"hlq_gemv_mx.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"],
+               "hlq_gemm_mfma.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
 
 
 def build(verbose: bool = False) -> str:
