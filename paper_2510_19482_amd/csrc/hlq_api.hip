@@ -239,10 +239,15 @@ hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const void *cons
     }
     if (M == 0) return HLQ_OK;
     if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
-    // one launch when the few-rows kernel carries M rows and the lookup formulation is not forced;
-    // otherwise the problems run one after the other on the stream, sharing the workspace
+    // one launch when the few-rows kernel carries M rows and the lookup formulation is not forced
     if (M == 1 || (M <= hlq_gemm_mx_rows_per_pass(items[0].dm.G) && hlq_gemm_uses_mx_rows(M)))
         return hlq_launch_gemv_batch(count, items, out, ws, (hipStream_t)stream);
+    // more rows on the matrix cores: one launch of the tiled kernel over all problems (K is not split there,
+    // so the workspace is not used)
+    if (count > 1 && hlq_gemm_uses_matrix_cores(M)) {
+        const hlq_status s = hlq_launch_gemm_mfma_batch(count, items, M, out, (hipStream_t)stream);
+        if (s != HLQ_ERR_UNSUPPORTED) return s;
+    }
     for (int i = 0; i < count; ++i) {
         hlq_status s = hlq_launch_gemm(items[i].dm, packed[i], X[i], M, ldx[i], Y[i], ldy[i], out, ws, (hipStream_t)stream);
         if (s != HLQ_OK) return s;

@@ -270,6 +270,9 @@ static bool use_mfma(int64_t M)
 // true if hlq_launch_gemm sends M rows (that fit one pass) to the few-rows matrix-core GEMV kernel
 bool hlq_gemm_uses_mx_rows(int64_t M) { return use_mfma(M) && g_gemm_path != 3; }
 
+// true if hlq_launch_gemm computes M rows on the matrix cores (either kernel)
+bool hlq_gemm_uses_matrix_cores(int64_t M) { return use_mfma(M); }
+
 size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M)
 {
     size_t a = hlq_gemm_lut_partial_bytes(dm, M);

@@ -66,11 +66,12 @@ struct WRegs {
                                // no wait for the load) before its first real use
 };
 
+// The work of one workgroup: column group bx (four 64-column tiles), K slice by, row block bz of one problem.
 template <int Q, int G, int MW>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const uint16_t *__restrict__ X, long ldx,
-                     int M, void *__restrict__ Y, long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks,
-                     int cps, int nslices, int out_f32)
+__device__ __forceinline__ void gemm_mfma_block(const char *__restrict__ packed, size_t col_bytes,
+                                                const uint16_t *__restrict__ X, long ldx, int M, void *__restrict__ Y,
+                                                long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks, int cps,
+                                                int nslices, int out_f32, int bx, int by, int bz)
 {
     using Regs = WRegs<Q, G>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
@@ -79,14 +80,14 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int tile = blockIdx.x * 4 + wave;
+    const int tile = bx * 4 + wave;
     const int tile_c = tile < ntiles ? tile : ntiles - 1;          // clamped: loads stay in bounds
     const int tw = hlq_tile_width(tile_c, N);
     const bool col_ok = tile < ntiles && lane < tw;
     const int lane_c = lane < tw ? lane : tw - 1;
     const char *tile_base = packed + (size_t)tile_c * HLQ_TILE_N * col_bytes;
-    const int m0 = blockIdx.z * ROWS;
-    const int cbeg = blockIdx.y * cps;
+    const int m0 = bz * ROWS;
+    const int cbeg = by * cps;
     const int cend = min(cbeg + cps, nchunks);
 
     auto load_w = [&](int c, Regs &R) {
@@ -264,10 +265,55 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
         }
     };
     const size_t n0 = (size_t)tile * HLQ_TILE_N;
-    if (nslices > 1) store_tiles(ws + ((size_t)blockIdx.y * M + rbase) * (size_t)N + n0, (long)N);
+    if (nslices > 1) store_tiles(ws + ((size_t)by * M + rbase) * (size_t)N + n0, (long)N);
     else if (out_f32) store_tiles((float *)Y + (size_t)rbase * ldy + n0, ldy);
     else store_tiles((_Float16 *)Y + (size_t)rbase * ldy + n0, ldy);
     (void)col_ok;
+}
+
+
+template <int Q, int G, int MW>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const uint16_t *__restrict__ X, long ldx,
+                     int M, void *__restrict__ Y, long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks,
+                     int cps, int nslices, int out_f32)
+{
+    gemm_mfma_block<Q, G, MW>(packed, col_bytes, X, ldx, M, Y, ldy, ws, N, ntiles, nchunks, cps, nslices, out_f32,
+                              (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+}
+
+// Several problems with the same q, G and M in one launch (hlq_lut_gemm_batch): workgroups are numbered
+// problem by problem, long-K problems first; inside a problem the column group runs fastest, then
+// the row block; K is not split (a grouped launch has workgroups enough), so nothing is left to reduce.
+// The table of first blocks arrives in preloaded scalar registers, as in the GEMV kernel.
+struct GemmProb {
+    const char *packed;
+    size_t col_bytes;
+    const uint16_t *X;
+    long ldx;
+    void *Y;
+    long ldy;
+    int N, ntiles, nchunks, colgroups, blk_begin;
+    unsigned cg_magic;   // ceil(2^32 / colgroups): local / colgroups = umulhi(local, cg_magic)
+};
+struct GemmProbs {
+    GemmProb p[HLQ_MAX_BATCH];
+};
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+template <int Q, int G, int MW>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+hlq_gemm_mfma_group_kernel(const int4v bb_lo, const int4v bb_hi, const int M, const int out_f32, const GemmProbs probs)
+{
+    const int blk = (int)blockIdx.x;   // the table is ascending, unused entries INT_MAX
+    const int pi = blk >= bb_hi.w ? 7 : blk >= bb_hi.z ? 6 : blk >= bb_hi.y ? 5 : blk >= bb_hi.x ? 4
+                 : blk >= bb_lo.w ? 3 : blk >= bb_lo.z ? 2 : blk >= bb_lo.y ? 1 : 0;
+    const GemmProb P = probs.p[pi];
+    const int local = blk - P.blk_begin;
+    const int rb = P.colgroups > 1 ? (int)__umulhi((unsigned)local, P.cg_magic) : local;
+    const int cg = local - rb * P.colgroups;
+    gemm_mfma_block<Q, G, MW>(P.packed, P.col_bytes, P.X, P.ldx, M, P.Y, P.ldy, nullptr, P.N, P.ntiles, P.nchunks,
+                              P.nchunks, 1, out_f32, cg, 0, rb);
 }
 
 __global__ void __launch_bounds__(256)
@@ -356,6 +402,31 @@ hlq_status launch_q(const HlqDims &dm, const MfmaPlan &p, const char *packed, co
     return HLQ_ERR_UNSUPPORTED;
 }
 
+template <int Q, int G>
+void launch_group_qg(int MW, unsigned nblocks, const int4v &lo, const int4v &hi, int M, int out_f32, const GemmProbs &pr,
+                     hipStream_t st)
+{
+    const size_t lds = (size_t)2 * 32 * MW * XROW * sizeof(_Float16);
+    switch (MW) {
+    case 1: hlq_gemm_mfma_group_kernel<Q, G, 1><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, pr); break;
+    case 2: hlq_gemm_mfma_group_kernel<Q, G, 2><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, pr); break;
+    default: hlq_gemm_mfma_group_kernel<Q, G, 4><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, pr); break;
+    }
+}
+
+template <int Q>
+hlq_status launch_group_q(int G, int MW, unsigned nblocks, const int4v &lo, const int4v &hi, int M, int out_f32,
+                          const GemmProbs &pr, hipStream_t st)
+{
+    switch (G) {
+    case 32: launch_group_qg<Q, 32>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
+    case 64: launch_group_qg<Q, 64>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
+    case 128: launch_group_qg<Q, 128>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
+    case 256: launch_group_qg<Q, 256>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
+    }
+    return HLQ_ERR_UNSUPPORTED;
+}
+
 } // namespace
 
 size_t hlq_gemm_mfma_partial_bytes(const HlqDims &dm, int64_t M)
@@ -386,5 +457,66 @@ hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uin
         hlq_gemm_mfma_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part, Y, (long)ldy, (int)M, dm.N,
                                                                                     p.nslices, out_f32);
     }
+    return hlq_hip_status(hipGetLastError());
+}
+
+// One launch for several problems of the same q, G and M.  HLQ_ERR_UNSUPPORTED if the launch cannot be
+// formed (the caller then runs the problems one after the other).
+hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, hipStream_t st)
+{
+    static_assert(HLQ_MAX_BATCH == 8, "the grouped kernel takes the first blocks of eight problems");
+    hlq_clear_stale_error();
+    if (count < 1 || count > HLQ_MAX_BATCH || M < 1 || M > 0x7fffffff) return HLQ_ERR_UNSUPPORTED;
+    const int MW = M > 64 ? 4 : (M > 32 ? 2 : 1);
+    const long rowblocks = (long)((M + 32 * MW - 1) / (32 * MW));
+    // workgroups start in block order: long-K problems first, so that the longest workgroups do not end alone
+    int order[HLQ_MAX_BATCH];
+    for (int i = 0; i < count; ++i) order[i] = i;
+    for (int i = 1; i < count; ++i)
+        for (int j = i; j > 0 && items[order[j]].dm.nchunks > items[order[j - 1]].dm.nchunks; --j) {
+            const int t = order[j];
+            order[j] = order[j - 1];
+            order[j - 1] = t;
+        }
+    GemmProbs pr;
+    int begin[HLQ_MAX_BATCH];
+    long blk = 0;
+    for (int i = 0; i < count; ++i) {
+        const HlqGemvItem &it = items[order[i]];
+        if (it.dm.q != items[0].dm.q || it.dm.G != items[0].dm.G) return HLQ_ERR_UNSUPPORTED;
+        GemmProb &p = pr.p[i];
+        p.packed = (const char *)it.packed;
+        p.col_bytes = it.dm.col_bytes;
+        p.X = it.x;
+        p.ldx = it.ldx;
+        p.Y = it.y;
+        p.ldy = it.ldy;
+        p.N = it.dm.N;
+        p.ntiles = it.dm.ntiles;
+        p.nchunks = it.dm.nchunks;
+        p.colgroups = (it.dm.ntiles + 3) / 4;
+        p.cg_magic = p.colgroups > 1 ? (unsigned)((0x100000000ULL + (unsigned)p.colgroups - 1) / (unsigned)p.colgroups) : 0u;
+        // the reciprocal is exact while local * colgroups < 2^32
+        if ((unsigned long long)p.colgroups * p.colgroups * rowblocks >= 0x100000000ULL) return HLQ_ERR_UNSUPPORTED;
+        p.blk_begin = (int)blk;
+        begin[i] = (int)blk;
+        blk += (long)p.colgroups * rowblocks;
+        if (blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
+    }
+    for (int i = count; i < HLQ_MAX_BATCH; ++i) {
+        pr.p[i] = pr.p[0];
+        begin[i] = 0x7fffffff;
+    }
+    const int4v lo = {begin[0], begin[1], begin[2], begin[3]}, hi = {begin[4], begin[5], begin[6], begin[7]};
+    const int out_f32 = out == HLQ_OUT_F32;
+    hlq_status s;
+    switch (items[0].dm.q) {
+    case 1: s = launch_group_q<1>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 2: s = launch_group_q<2>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 3: s = launch_group_q<3>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 4: s = launch_group_q<4>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    default: return HLQ_ERR_UNSUPPORTED;
+    }
+    if (s != HLQ_OK) return s;
     return hlq_hip_status(hipGetLastError());
 }
