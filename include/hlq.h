@@ -143,8 +143,9 @@ HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const vo
  * leading dimension ldx[i] >= K_i (a multiple of 8 for M > 1), Y_i with ldy[i] >= N_i; descs,
  * packed, X, ldx, Y, ldy are host arrays of `count` (1..8) entries.  Up to what one pass of the
  * few-rows kernel carries (8 rows at G >= 128, 4 at G = 64, 2 at G = 32) that kernel takes all
- * problems; above it one launch of the tiled matrix-core kernel does (no split of K, no second
- * kernel: the seven GEMMs of an 8B layer at M = 2048 run 1.3x faster than as seven calls).  If the
+ * problems; above it one launch of the tiled matrix-core kernel does (plus one that adds the
+ * partial sums when K is cut: the seven GEMMs of an 8B layer run 1.3x faster than as seven calls
+ * at M = 2048 and 2x faster at M = 16).  If the
  * lookup formulation is forced the problems run one after the other on the stream.  M = 0 is a
  * no-op.
  *   ws / ws_bytes: workspace of at least hlq_gemm_batch_workspace_bytes(count, descs, M). */

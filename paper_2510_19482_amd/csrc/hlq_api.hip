@@ -97,18 +97,26 @@ hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, size_t *b
     return HLQ_OK;
 }
 
+static size_t batch_partial_bytes(int count, const HlqDims *dms, int64_t M)
+{
+    return M > 1 ? hlq_gemm_mfma_batch_partial_bytes(count, dms, M) : 0;
+}
+
 hlq_status hlq_gemm_batch_workspace_bytes(int count, const hlq_desc *descs, int64_t M, size_t *bytes)
 {
     if (!descs || !bytes) return HLQ_ERR_NULL;
     if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
     if (M < 0) return HLQ_ERR_BAD_STRIDE;
     size_t b = HLQ_WS_COUNTER_BYTES;
+    HlqDims dms[HLQ_MAX_BATCH];
     for (int i = 0; i < count; ++i) {
-        HlqDims dm;
-        hlq_status s = hlq_check_desc(&descs[i], &dm);
+        hlq_status s = hlq_check_desc(&descs[i], &dms[i]);
         if (s != HLQ_OK) return s;
-        b += M <= 1 ? hlq_gemv_partial_bytes(dm) : hlq_gemm_partial_bytes(dm, M);
+        b += M <= 1 ? hlq_gemv_partial_bytes(dms[i]) : hlq_gemm_partial_bytes(dms[i], M);
     }
+    // the grouped launch of the tiled kernel splits K on its own terms
+    const size_t grouped = HLQ_WS_COUNTER_BYTES + batch_partial_bytes(count, dms, M);
+    if (grouped > b) b = grouped;
     *bytes = (b + 255u) & ~(size_t)255u;
     return HLQ_OK;
 }
@@ -238,14 +246,20 @@ hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const void *cons
         need += M <= 1 ? hlq_gemv_partial_bytes(items[i].dm) : hlq_gemm_partial_bytes(items[i].dm, M);
     }
     if (M == 0) return HLQ_OK;
+    {
+        HlqDims dms[HLQ_MAX_BATCH];
+        for (int i = 0; i < count; ++i) dms[i] = items[i].dm;
+        const size_t grouped = HLQ_WS_COUNTER_BYTES + batch_partial_bytes(count, dms, M);
+        if (grouped > need) need = grouped;
+    }
     if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
     // one launch when the few-rows kernel carries M rows and the lookup formulation is not forced
     if (M == 1 || (M <= hlq_gemm_mx_rows_per_pass(items[0].dm.G) && hlq_gemm_uses_mx_rows(M)))
         return hlq_launch_gemv_batch(count, items, out, ws, (hipStream_t)stream);
-    // more rows on the matrix cores: one launch of the tiled kernel over all problems (K is not split there,
-    // so the workspace is not used)
+    // more rows on the matrix cores: one launch of the tiled kernel over all problems (and one for the partial
+    // sums where K is split)
     if (count > 1 && hlq_gemm_uses_matrix_cores(M)) {
-        const hlq_status s = hlq_launch_gemm_mfma_batch(count, items, M, out, (hipStream_t)stream);
+        const hlq_status s = hlq_launch_gemm_mfma_batch(count, items, M, out, ws, (hipStream_t)stream);
         if (s != HLQ_ERR_UNSUPPORTED) return s;
     }
     for (int i = 0; i < count; ++i) {

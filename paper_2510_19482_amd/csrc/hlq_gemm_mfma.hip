@@ -284,8 +284,9 @@ hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const ui
 
 // Several problems with the same q, G and M in one launch (hlq_lut_gemm_batch): workgroups are numbered
 // problem by problem, long-K problems first; inside a problem the column group runs fastest, then
-// the row block; K is not split (a grouped launch has workgroups enough), so nothing is left to reduce.
-// The table of first blocks arrives in preloaded scalar registers, as in the GEMV kernel.
+// the K slice, then the row block.  The table of first blocks arrives in preloaded scalar
+// registers, as in the GEMV kernel.  Problems whose K is split leave fp32 partial sums that
+// hlq_gemm_mfma_group_reduce_kernel adds, again in one launch for all of them.
 struct GemmProb {
     const char *packed;
     size_t col_bytes;
@@ -293,27 +294,62 @@ struct GemmProb {
     long ldx;
     void *Y;
     long ldy;
-    int N, ntiles, nchunks, colgroups, blk_begin;
+    float *part;         // [nslices][M][N] partial sums (nslices > 1)
+    int N, ntiles, nchunks, colgroups, blk_begin, cps, nslices;
     unsigned cg_magic;   // ceil(2^32 / colgroups): local / colgroups = umulhi(local, cg_magic)
+    unsigned ns_magic;   // the same for nslices
 };
 struct GemmProbs {
     GemmProb p[HLQ_MAX_BATCH];
 };
 typedef int int4v __attribute__((ext_vector_type(4)));
 
+// index of the problem that owns block `blk`: the table is ascending, unused entries INT_MAX
+__device__ __forceinline__ int group_problem_of(const int4v &bb_lo, const int4v &bb_hi, int blk)
+{
+    return blk >= bb_hi.w ? 7 : blk >= bb_hi.z ? 6 : blk >= bb_hi.y ? 5 : blk >= bb_hi.x ? 4
+         : blk >= bb_lo.w ? 3 : blk >= bb_lo.z ? 2 : blk >= bb_lo.y ? 1 : 0;
+}
+
 template <int Q, int G, int MW>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 hlq_gemm_mfma_group_kernel(const int4v bb_lo, const int4v bb_hi, const int M, const int out_f32, const GemmProbs probs)
 {
-    const int blk = (int)blockIdx.x;   // the table is ascending, unused entries INT_MAX
-    const int pi = blk >= bb_hi.w ? 7 : blk >= bb_hi.z ? 6 : blk >= bb_hi.y ? 5 : blk >= bb_hi.x ? 4
-                 : blk >= bb_lo.w ? 3 : blk >= bb_lo.z ? 2 : blk >= bb_lo.y ? 1 : 0;
-    const GemmProb P = probs.p[pi];
+    const int blk = (int)blockIdx.x;
+    const GemmProb P = probs.p[group_problem_of(bb_lo, bb_hi, blk)];
     const int local = blk - P.blk_begin;
-    const int rb = P.colgroups > 1 ? (int)__umulhi((unsigned)local, P.cg_magic) : local;
-    const int cg = local - rb * P.colgroups;
-    gemm_mfma_block<Q, G, MW>(P.packed, P.col_bytes, P.X, P.ldx, M, P.Y, P.ldy, nullptr, P.N, P.ntiles, P.nchunks,
-                              P.nchunks, 1, out_f32, cg, 0, rb);
+    const int t = P.colgroups > 1 ? (int)__umulhi((unsigned)local, P.cg_magic) : local;
+    const int cg = local - t * P.colgroups;
+    const int rb = P.nslices > 1 ? (int)__umulhi((unsigned)t, P.ns_magic) : t;
+    const int sl = t - rb * P.nslices;
+    gemm_mfma_block<Q, G, MW>(P.packed, P.col_bytes, P.X, P.ldx, M, P.Y, P.ldy, P.part, P.N, P.ntiles, P.nchunks,
+                              P.cps, P.nslices, out_f32, cg, sl, rb);
+}
+
+// adds the partial sums of all problems of a grouped launch whose K was split; 256 outputs per block
+struct GemmRedProb {
+    const float *part;
+    void *Y;
+    long ldy;
+    int N, nslices, blk_begin;
+};
+struct GemmRedProbs {
+    GemmRedProb p[HLQ_MAX_BATCH];
+};
+
+__global__ void __launch_bounds__(256)
+hlq_gemm_mfma_group_reduce_kernel(const int4v bb_lo, const int4v bb_hi, const int M, const int out_f32,
+                                  const GemmRedProbs probs)
+{
+    const int blk = (int)blockIdx.x;
+    const GemmRedProb P = probs.p[group_problem_of(bb_lo, bb_hi, blk)];
+    const size_t i = (size_t)(blk - P.blk_begin) * 256 + threadIdx.x;
+    const size_t total = (size_t)M * P.N;
+    if (i >= total) return;
+    float a = 0.f;
+    for (int s = 0; s < P.nslices; ++s) a += P.part[(size_t)s * total + i];
+    const size_t m = i / P.N, n = i % P.N;
+    store_out(P.Y, m * P.ldy + n, a, out_f32);
 }
 
 __global__ void __launch_bounds__(256)
@@ -460,15 +496,53 @@ hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uin
     return hlq_hip_status(hipGetLastError());
 }
 
+// Work split of a grouped launch.  Every problem is cut along K into slices of about the same number of
+// chunks, chosen so that the launch has about 512 workgroups (one round at two workgroups per CU);
+// with many rows nothing is cut.  Used by the launch and by the workspace size.
+struct GroupPlan {
+    int MW;
+    long rowblocks;
+    int cps[HLQ_MAX_BATCH], nslices[HLQ_MAX_BATCH];
+};
+
+static GroupPlan plan_group(int count, const HlqDims *dms, int64_t M)
+{
+    GroupPlan g;
+    g.MW = M > 64 ? 4 : (M > 32 ? 2 : 1);
+    g.rowblocks = (long)((M + 32 * g.MW - 1) / (32 * g.MW));
+    double units = 0.0;   // workgroup-chunks of the whole launch
+    for (int i = 0; i < count; ++i) units += (double)((dms[i].ntiles + 3) / 4) * g.rowblocks * dms[i].nchunks;
+    long target = (long)(units / 512.0 + 0.999);
+    if (target < 2) target = 2;
+    for (int i = 0; i < count; ++i) {
+        int ns = (int)((dms[i].nchunks + target - 1) / target);
+        if (ns < 1) ns = 1;
+        int cps = (dms[i].nchunks + ns - 1) / ns;
+        cps = (cps + 1) & ~1;   // the chunk loop alternates two register sets
+        g.cps[i] = cps;
+        g.nslices[i] = (dms[i].nchunks + cps - 1) / cps;
+    }
+    return g;
+}
+
+size_t hlq_gemm_mfma_batch_partial_bytes(int count, const HlqDims *dms, int64_t M)
+{
+    if (count < 2 || M < 1) return 0;
+    const GroupPlan g = plan_group(count, dms, M);
+    size_t b = 0;
+    for (int i = 0; i < count; ++i)
+        if (g.nslices[i] > 1) b += (size_t)g.nslices[i] * (size_t)M * (size_t)dms[i].N * sizeof(float);
+    return b;
+}
+
 // One launch for several problems of the same q, G and M.  HLQ_ERR_UNSUPPORTED if the launch cannot be
 // formed (the caller then runs the problems one after the other).
-hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, hipStream_t st)
+hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, void *ws,
+                                      hipStream_t st)
 {
-    static_assert(HLQ_MAX_BATCH == 8, "the grouped kernel takes the first blocks of eight problems");
+    static_assert(HLQ_MAX_BATCH == 8, "the grouped kernels take the first blocks of eight problems");
     hlq_clear_stale_error();
     if (count < 1 || count > HLQ_MAX_BATCH || M < 1 || M > 0x7fffffff) return HLQ_ERR_UNSUPPORTED;
-    const int MW = M > 64 ? 4 : (M > 32 ? 2 : 1);
-    const long rowblocks = (long)((M + 32 * MW - 1) / (32 * MW));
     // workgroups start in block order: long-K problems first, so that the longest workgroups do not end alone
     int order[HLQ_MAX_BATCH];
     for (int i = 0; i < count; ++i) order[i] = i;
@@ -478,9 +552,16 @@ hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64
             order[j] = order[j - 1];
             order[j - 1] = t;
         }
+    HlqDims dms[HLQ_MAX_BATCH];
+    for (int i = 0; i < count; ++i) dms[i] = items[order[i]].dm;
+    const GroupPlan g = plan_group(count, dms, M);
     GemmProbs pr;
-    int begin[HLQ_MAX_BATCH];
-    long blk = 0;
+    GemmRedProbs rp;
+    int begin[HLQ_MAX_BATCH], rbegin[HLQ_MAX_BATCH];
+    long blk = 0, rblk = 0;
+    int nred = 0;
+    float *part = (float *)((char *)ws + HLQ_WS_COUNTER_BYTES);
+    auto magic = [](int d) { return d > 1 ? (unsigned)((0x100000000ULL + (unsigned)d - 1) / (unsigned)d) : 0u; };
     for (int i = 0; i < count; ++i) {
         const HlqGemvItem &it = items[order[i]];
         if (it.dm.q != items[0].dm.q || it.dm.G != items[0].dm.G) return HLQ_ERR_UNSUPPORTED;
@@ -491,17 +572,35 @@ hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64
         p.ldx = it.ldx;
         p.Y = it.y;
         p.ldy = it.ldy;
+        p.part = part;
         p.N = it.dm.N;
         p.ntiles = it.dm.ntiles;
         p.nchunks = it.dm.nchunks;
         p.colgroups = (it.dm.ntiles + 3) / 4;
-        p.cg_magic = p.colgroups > 1 ? (unsigned)((0x100000000ULL + (unsigned)p.colgroups - 1) / (unsigned)p.colgroups) : 0u;
-        // the reciprocal is exact while local * colgroups < 2^32
-        if ((unsigned long long)p.colgroups * p.colgroups * rowblocks >= 0x100000000ULL) return HLQ_ERR_UNSUPPORTED;
+        p.cps = g.cps[i];
+        p.nslices = g.nslices[i];
+        p.cg_magic = magic(p.colgroups);
+        p.ns_magic = magic(p.nslices);
+        const unsigned long long blocks = (unsigned long long)p.colgroups * p.nslices * g.rowblocks;
+        // the reciprocals are exact while (largest dividend) * divisor < 2^32
+        if (blocks * p.colgroups >= 0x100000000ULL || blocks * p.nslices >= 0x100000000ULL) return HLQ_ERR_UNSUPPORTED;
         p.blk_begin = (int)blk;
         begin[i] = (int)blk;
-        blk += (long)p.colgroups * rowblocks;
+        blk += (long)blocks;
         if (blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
+        if (p.nslices > 1) {
+            GemmRedProb &r = rp.p[nred];
+            r.part = part;
+            r.Y = it.y;
+            r.ldy = it.ldy;
+            r.N = it.dm.N;
+            r.nslices = p.nslices;
+            r.blk_begin = (int)rblk;
+            rbegin[nred++] = (int)rblk;
+            rblk += (long)(((size_t)M * it.dm.N + 255) / 256);
+            if (rblk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
+            part += (size_t)p.nslices * (size_t)M * (size_t)it.dm.N;
+        }
     }
     for (int i = count; i < HLQ_MAX_BATCH; ++i) {
         pr.p[i] = pr.p[0];
@@ -511,12 +610,20 @@ hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64
     const int out_f32 = out == HLQ_OUT_F32;
     hlq_status s;
     switch (items[0].dm.q) {
-    case 1: s = launch_group_q<1>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
-    case 2: s = launch_group_q<2>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
-    case 3: s = launch_group_q<3>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
-    case 4: s = launch_group_q<4>(items[0].dm.G, MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 1: s = launch_group_q<1>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 2: s = launch_group_q<2>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 3: s = launch_group_q<3>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 4: s = launch_group_q<4>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
     default: return HLQ_ERR_UNSUPPORTED;
     }
     if (s != HLQ_OK) return s;
+    if (nred > 0) {
+        for (int i = nred; i < HLQ_MAX_BATCH; ++i) {
+            rp.p[i] = rp.p[0];
+            rbegin[i] = 0x7fffffff;
+        }
+        const int4v rlo = {rbegin[0], rbegin[1], rbegin[2], rbegin[3]}, rhi = {rbegin[4], rbegin[5], rbegin[6], rbegin[7]};
+        hlq_gemm_mfma_group_reduce_kernel<<<(unsigned)rblk, 256, 0, st>>>(rlo, rhi, (int)M, out_f32, rp);
+    }
     return hlq_hip_status(hipGetLastError());
 }

@@ -116,7 +116,9 @@ hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uin
                                 int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);
 hlq_status hlq_gemm_path_override(int path);
 bool hlq_gemm_uses_matrix_cores(int64_t M);
-hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, hipStream_t st);
+hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, void *ws,
+                                      hipStream_t st);
+size_t hlq_gemm_mfma_batch_partial_bytes(int count, const HlqDims *dms, int64_t M);
 int hlq_gemv_mx_rows_per_set(int G);
 int hlq_gemm_mx_rows_per_pass(int G);
 bool hlq_gemm_uses_mx_rows(int64_t M);
