@@ -17,10 +17,11 @@ FLAGS = [
     "-Wno-unused-command-line-argument",
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
-# per-file additions.  The matrix-core GEMV kernel takes the table of first blocks and the flags as its
-# first ten scalar arguments and has them preloaded into scalar registers at wavefront start.
+# per-file additions.  The GEMV kernels take the table of first blocks and the output flag as their
+# first nine scalar arguments and have them preloaded into scalar registers at wavefront start.
 # The tiled GEMM kernel gets its leading arguments (pointers, strides, M) the same way.
-EXTRA_FLAGS = {"hlq_gemv_mx.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=10"],
+EXTRA_FLAGS = {"hlq_gemv_mx.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=9"],
+               "hlq_gemv.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=9"],
                "hlq_gemm_mfma.hip": ["-mllvm", "-amdgpu-kernarg-preload-count=14"]}
 
 

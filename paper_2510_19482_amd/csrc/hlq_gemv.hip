@@ -189,8 +189,9 @@ constexpr int gemv_nbuf(int Q, int G, int TN) { return gemv_weight(Q, G, TN) <= 
 
 template <int Q, int G, int TN>
 __global__ void __launch_bounds__(gemv_max_threads(Q, G, TN))
-hlq_gemv_kernel(const GemvBatch b)
+hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, const GemvProbs probs)
 {
+    struct { int out_f32; } b = {out_f32_flag};
     using Regs = ChunkRegs<Q, G, TN>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
     constexpr int NBUF = gemv_nbuf(Q, G, TN);
@@ -200,7 +201,7 @@ hlq_gemv_kernel(const GemvBatch b)
     float *red = lds + W * (HLQ_GEMV_TABLE_BYTES / 4);
 
     // ---- which problem, which column tile group, which K slice ---------------------------------
-    const GemvProb P = b.p[gemv_problem_of(b, (int)blockIdx.x)];   // a copy: one burst of scalar loads
+    const GemvProb P = probs.p[gemv_problem_of(bb_lo, bb_hi, (int)blockIdx.x)];   // a copy: one burst of scalar loads
     int tg, slice;
     gemv_split_block(P, (int)blockIdx.x - P.blk_begin, tg, slice);
 
@@ -396,10 +397,12 @@ template <int Q, int G>
 void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int TN, hipStream_t st)
 {
     const dim3 blk(64 * W);
+    const GemvKernelArgs a = gemv_kernel_args(b);
     if (TN == 2) {
-        if constexpr (gemv_two_tiles_ok(Q, G)) hlq_gemv_kernel<Q, G, 2><<<nblocks, blk, gemv_lds_bytes(W, 2), st>>>(b);
+        if constexpr (gemv_two_tiles_ok(Q, G))
+            hlq_gemv_kernel<Q, G, 2><<<nblocks, blk, gemv_lds_bytes(W, 2), st>>>(a.lo, a.hi, a.out_f32, a.probs);
     } else {
-        hlq_gemv_kernel<Q, G, 1><<<nblocks, blk, gemv_lds_bytes(W, 1), st>>>(b);
+        hlq_gemv_kernel<Q, G, 1><<<nblocks, blk, gemv_lds_bytes(W, 1), st>>>(a.lo, a.hi, a.out_f32, a.probs);
     }
 }
 

@@ -21,14 +21,44 @@ struct GemvProb {
     long ldx, ldy;
 };
 
-// The head of the block (first blocks of all problems, flags) is what every workgroup needs before it
-// knows its problem: kept together so that one scalar load fetches it, a second one the problem.
+// Host-side description of a launch.
 struct GemvBatch {
-    int blk_begin[HLQ_MAX_BATCH];   // ascending; unused entries INT_MAX
+    int blk_begin[HLQ_MAX_BATCH];   // first block of every problem, ascending; unused entries INT_MAX
     int count;
     int out_f32;
     GemvProb p[HLQ_MAX_BATCH];
 };
+
+// What the kernels take: the first blocks of the problems and the flag as leading scalar arguments --
+// they are preloaded into scalar registers when a wavefront starts (kernarg preload, a per-file
+// compiler option), so a workgroup finds its problem without a trip to memory -- and the problem
+// records, of which the workgroup copies its own with one burst of scalar loads.
+typedef int int4v __attribute__((ext_vector_type(4)));
+struct GemvProbs {
+    GemvProb p[HLQ_MAX_BATCH];
+};
+struct GemvKernelArgs {
+    int4v lo, hi;
+    int out_f32;
+    GemvProbs probs;
+};
+inline GemvKernelArgs gemv_kernel_args(const GemvBatch &b)
+{
+    static_assert(HLQ_MAX_BATCH == 8, "the kernels take the first blocks of eight problems");
+    GemvKernelArgs a;
+    a.lo = (int4v){b.blk_begin[0], b.blk_begin[1], b.blk_begin[2], b.blk_begin[3]};
+    a.hi = (int4v){b.blk_begin[4], b.blk_begin[5], b.blk_begin[6], b.blk_begin[7]};
+    a.out_f32 = b.out_f32;
+    for (int i = 0; i < HLQ_MAX_BATCH; ++i) a.probs.p[i] = b.p[i];
+    return a;
+}
+
+// index of the problem that owns workgroup `blk`: the table is ascending, unused entries INT_MAX
+__device__ __forceinline__ int gemv_problem_of(const int4v &bb_lo, const int4v &bb_hi, int blk)
+{
+    return blk >= bb_hi.w ? 7 : blk >= bb_hi.z ? 6 : blk >= bb_hi.y ? 5 : blk >= bb_hi.x ? 4
+         : blk >= bb_lo.w ? 3 : blk >= bb_lo.z ? 2 : blk >= bb_lo.y ? 1 : 0;
+}
 
 // (tile group, K slice) of workgroup `local` of a problem: local = tg * nslices + slice, without an
 // integer division (emulated ones cost some 30 dependent instructions at the head of every workgroup)
@@ -38,14 +68,6 @@ __device__ __forceinline__ void gemv_split_block(const GemvProb &P, int local, i
     slice = local - tg * P.nslices;
 }
 
-// index of the problem that owns workgroup `blk` (branch-free: the table is sorted)
-__device__ __forceinline__ int gemv_problem_of(const GemvBatch &b, int blk)
-{
-    int pi = 0;
-#pragma unroll
-    for (int i = 1; i < HLQ_MAX_BATCH; ++i) pi += blk >= b.blk_begin[i] ? 1 : 0;
-    return pi;
-}
 
 __device__ __forceinline__ float h2f(uint16_t h) { return (float)__builtin_bit_cast(_Float16, h); }
 

@@ -117,21 +117,11 @@ constexpr int mx_nbuf(int, int) { return HLQ_MX_NBUF; }
 constexpr int mx_nbuf(int, int) { return 2; }
 #endif
 
-// The first blocks of the problems and the flags are separate scalar arguments at the head of the
-// argument block: they are preloaded into scalar registers when a wavefront starts (kernarg
-// preload), so finding the problem costs no trip to memory; the problem record is then one burst
-// of scalar loads.
-struct GemvProbs {
-    GemvProb p[HLQ_MAX_BATCH];
-};
-typedef int int4v __attribute__((ext_vector_type(4)));
-
 template <int Q, int G, int NS, bool BATCHED>
 __global__ void __launch_bounds__(512)
-hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int count, const int out_f32_flag, const GemvProbs probs)
+hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, const GemvProbs probs)
 {
     struct { int out_f32; } b = {out_f32_flag};
-    (void)count;
     constexpr int NROW = mx_rows(G, NS, BATCHED);
     using Regs = MxRegs<Q, G, NROW>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
@@ -142,10 +132,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int count, const 
     const int W = (int)(blockDim.x >> 6);
     extern __shared__ __attribute__((aligned(256))) char lds[];
 
-    // the table is ascending, unused entries INT_MAX
-    const int blk = (int)blockIdx.x;
-    const int pi = blk >= bb_hi.w ? 7 : blk >= bb_hi.z ? 6 : blk >= bb_hi.y ? 5 : blk >= bb_hi.x ? 4
-                 : blk >= bb_lo.w ? 3 : blk >= bb_lo.z ? 2 : blk >= bb_lo.y ? 1 : 0;
+    const int pi = gemv_problem_of(bb_lo, bb_hi, (int)blockIdx.x);
     const GemvProb P = probs.p[pi];   // a copy: one burst of scalar loads
     int tg, slice;
     gemv_split_block(P, (int)blockIdx.x - P.blk_begin, tg, slice);
@@ -479,17 +466,13 @@ template <int Q, int G>
 void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int nsets, hipStream_t st)
 {
     const dim3 blk(64 * W);
-    const int4v lo = {b.blk_begin[0], b.blk_begin[1], b.blk_begin[2], b.blk_begin[3]};
-    const int4v hi = {b.blk_begin[4], b.blk_begin[5], b.blk_begin[6], b.blk_begin[7]};
-    static_assert(HLQ_MAX_BATCH == 8, "the kernel takes the first blocks of eight problems");
-    GemvProbs pr;
-    for (int i = 0; i < HLQ_MAX_BATCH; ++i) pr.p[i] = b.p[i];
+    const GemvKernelArgs a = gemv_kernel_args(b);
     if (nsets == 0)
-        hlq_gemv_mx_kernel<Q, G, 1, false><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, 1), st>>>(lo, hi, b.count, b.out_f32, pr);
+        hlq_gemv_mx_kernel<Q, G, 1, false><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, 1), st>>>(a.lo, a.hi, a.out_f32, a.probs);
     else if (nsets == 1)
-        hlq_gemv_mx_kernel<Q, G, 1, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 1, true)), st>>>(lo, hi, b.count, b.out_f32, pr);
+        hlq_gemv_mx_kernel<Q, G, 1, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 1, true)), st>>>(a.lo, a.hi, a.out_f32, a.probs);
     else
-        hlq_gemv_mx_kernel<Q, G, 2, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 2, true)), st>>>(lo, hi, b.count, b.out_f32, pr);
+        hlq_gemv_mx_kernel<Q, G, 2, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 2, true)), st>>>(a.lo, a.hi, a.out_f32, a.probs);
 }
 
 template <int Q>
