@@ -76,3 +76,32 @@ def test_fused_decode_shapes(shape):
     # the fused projections of the decode loop bench.py times (q|k|v as one N = 6144 GEMV, gate|up as
     # one N = 28672 GEMV); sampled columns for the wide one
     check(shape, 2, 128, 1, "fused", False, ncols=None if shape.N <= 8192 else 2048)
+
+
+def test_config4_prefill_whole_layer_one_grouped_launch():
+    # the launch bench.py times for the M = 2048 figure: all seven matrices of the 8B layer in one
+    # hlq_lut_gemm_batch call, every row, sampled columns against the C oracle
+    from paper_2510_19482_amd import binding as B
+    from gpu_util import dev
+    M, q, G = 2048, 2, 128
+    shapes = synth.LLAMA31_8B_LAYER
+    descs, packs, Xs, Ys, refs, colsets = [], [], [], [], [], []
+    for s in shapes:
+        say("config cfg4 grouped", s.name, s.K, s.N)
+        codes, S, Z = synth.make_weight(s.K, s.N, q, G, "cfg4g", s.name)
+        X = synth.make_x(M, s.K, "cfg4g", s.name, outliers=True)
+        d, p = pack_on_gpu(codes, S, Z, q, G)
+        cols = synth.sample_columns(s.N, 24, "cfg4g", s.name)
+        refs.append(c_oracle.gemm_f64(X, codes, S, Z, q, G, cols=cols))
+        colsets.append(cols)
+        descs.append(d); packs.append(p); Xs.append(dev(X))
+        Ys.append(torch.empty((M, s.N), dtype=torch.float16, device="cuda"))
+        del codes, S, Z, X
+    B.GemmBatch(descs, packs, Xs, Ys).launch()
+    torch.cuda.synchronize()
+    for s, Y, ref, cols in zip(shapes, Ys, refs, colsets):
+        err = O.row_rel_err(Y[:, torch.from_numpy(cols).cuda()].float().cpu().numpy().astype(np.float64), ref)
+        say("   ", s.name, "max row err", float(err.max()))
+        assert err.max() <= TOL, s.name
+    del packs, Xs, Ys
+    torch.cuda.empty_cache()
