@@ -9,7 +9,10 @@
  * of four gets a 16-entry table of the partial sums sum_r bit_r(i) * x[4t+r], and every
  * 4-bit slice of every bit-plane indexes that table; looked-up entries are added in
  * fp32, multiplied once per (plane, quant group) by s_j, and z enters as
- * z * (sum of the group's activations).
+ * z * (sum of the group's activations).  By default the per-plane binary dot products are
+ * taken on the matrix cores instead of through tables (same sums, see hlq_set_gemv_path),
+ * and for many rows W^ is rebuilt tile by tile in registers (see hlq_set_gemm_path).
+ * hlq_quantize produces the codes, scales and zeros from real-valued weights (Alg. 1).
  *
  * Conventions
  *   - Every pointer below is a DEVICE pointer unless it is marked "host".
