@@ -26,7 +26,9 @@ Pins (tests/test_oracle_*.py): the bit-plane worked example of App. B; the
 bits-per-weight figures of Table 1 and the model sizes of Table 3; exact rational
 brute force on tiny inputs; the uniform special case s_j = 2^j * Delta (Alg. 1 init)
 against textbook integer dequantisation; one-hot activations; all-zero / all-one
-planes; linearity; LUT == dequant; mirror == plain.  No function here is unpinned.
+planes; linearity; LUT == dequant; mirror == plain; the lossy-table variant (App. D, Table
+Quantization: fp16 or int8 entries) equals the plain lookup path on entries the storage type
+holds exactly.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -222,6 +224,44 @@ def gemm_lut_mirror(X, codes, scales, zeros, q: int, G: int) -> np.ndarray:
                     p += np.where(hi, -v, v)               # other half by negation
                 Y[m] += s_hat[j, g] * p
             Y[m] += z_hat[g] * xsum[g]
+    return Y
+
+
+def quantise_tables(T: np.ndarray, entry: str) -> np.ndarray:
+    """Lossy table storage (App. D, Table Quantization).  T [tables, 16] fp64 -> the values a lookup
+    returns when entries are stored as
+      "fp16": IEEE binary16, round to nearest even (the paper's NEON tables);
+      "int8": one scale per table, max|entry| / 127, entries rounded to the nearest integer in
+              [-127, 127] (the paper only says "mapping FP16 table values to int8"; a scale per
+              16-entry table is the finest choice, so this is the smallest error the option can have)."""
+    if entry == "fp16":
+        return T.astype(np.float16).astype(np.float64)
+    if entry == "int8":
+        scale = np.abs(T).max(axis=1, keepdims=True) / 127.0
+        safe = np.where(scale > 0, scale, 1.0)
+        return np.clip(np.rint(T / safe), -127, 127) * scale
+    raise ValueError(entry)
+
+
+def gemm_lut_lossy_tables(X, codes, scales, zeros, q: int, G: int, entry: str) -> np.ndarray:
+    """gemm_lut with quantised table entries; everything else (accumulation, scales, zero term with the
+    exact activation sums) as in gemm_lut, so the difference to it is the table precision alone."""
+    M, K = X.shape
+    N = codes.shape[1]
+    planes = bit_planes(codes, q)
+    idx = [nibbles(planes[j]) for j in range(q)]
+    tpg = G // LUT_GROUP
+    Y = np.zeros((M, N), dtype=np.float64)
+    for m in range(M):
+        T = quantise_tables(build_tables(X[m]), entry)
+        xsum = X[m].astype(np.float64).reshape(K // G, G).sum(axis=1)
+        for g in range(K // G):
+            for j in range(q):
+                p = np.zeros(N, dtype=np.float64)
+                for t in range(g * tpg, (g + 1) * tpg):
+                    p += T[t, idx[j][t]]
+                Y[m] += scales[j, g].astype(np.float64) * p
+            Y[m] += zeros[g].astype(np.float64) * xsum[g]
     return Y
 
 

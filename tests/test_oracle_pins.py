@@ -209,3 +209,28 @@ def test_row_rel_err():
     ref = np.array([[1.0, -4.0], [0.5, 0.25]])
     y = ref + np.array([[0.004, 0.0], [0.0, 0.001]])
     np.testing.assert_allclose(O.row_rel_err(y, ref), [0.001, 0.002])
+
+
+def test_lossy_table_variants_error_levels():
+    # App. D, Table Quantization: what storing the 16-entry tables in fp16 or int8 costs, measured with
+    # everything else exact.  Pins of the function itself: with table entries that fp16 holds
+    # exactly (small integers) the fp16 variant IS the lookup path; int8 with entries that are
+    # multiples of max/127 is exact too.
+    K, N, q, G = 256, 16, 2, 64
+    codes, S, Z = synth.make_weight(K, N, q, G, "lossy-pin")
+    Xi = (synth.make_x(2, K, "lossy-pin").astype(np.float64) * 4).round().clip(-8, 8).astype(np.float16)
+    assert np.array_equal(O.gemm_lut_lossy_tables(Xi, codes, S, Z, q, G, "fp16"), O.gemm_lut(Xi, codes, S, Z, q, G))
+    T = np.array([[0.0, 127.0, -127.0, 64.0, 1.0, -3.0] + [0.0] * 10])
+    assert np.array_equal(O.quantise_tables(T, "int8"), T)
+    assert np.array_equal(O.quantise_tables(np.zeros((2, 16)), "int8"), np.zeros((2, 16)))
+    # error levels on a layer-like case (K = 4096, activations with outlier channels): fp16 entries stay
+    # inside the 2e-3 bar with a wide margin, int8 entries (one scale per table) do not
+    K, N = 4096, 128
+    codes, S, Z = synth.make_weight(K, N, q, 128, "lossy")
+    X = synth.make_x(3, K, "lossy", outliers=True)
+    ref = O.gemm_dequant(X, codes, S, Z, q, 128)
+    e16 = O.row_rel_err(O.gemm_lut_lossy_tables(X, codes, S, Z, q, 128, "fp16"), ref)
+    e8 = O.row_rel_err(O.gemm_lut_lossy_tables(X, codes, S, Z, q, 128, "int8"), ref)
+    assert 2e-5 < e16.max() < 1e-3
+    assert 1e-3 < e8.min() and e8.max() < 2e-2
+    assert e8.min() > 4 * e16.max()
