@@ -194,6 +194,16 @@ HLQ_API hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uin
                         int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
                         size_t ws_bytes, void *stream);
 
+/* Measurement helper, no part of the method: read `bytes` of device memory once with 128-bit
+ * loads, `blocks` workgroups of 256 lanes each taking one contiguous share (0 = 2048), and store
+ * one checksum word per workgroup to `sink`.  Benchmarks time it on as many bytes as a GEMV launch
+ * reads, as the read-only reference beside the published bandwidth figure.
+ *   src 16-byte aligned, bytes a multiple of 16 (else HLQ_ERR_BAD_STRIDE); 0 <= blocks <= 65536
+ *   (else HLQ_ERR_UNSUPPORTED); sink_bytes >= 4 * (workgroups launched) <= 4 * max(blocks, 1) resp.
+ *   8192 for blocks = 0 (else HLQ_ERR_BUFFER_TOO_SMALL). */
+HLQ_API hlq_status hlq_stream_read(const void *src, size_t bytes, int blocks, void *sink, size_t sink_bytes,
+                                   void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -76,6 +76,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_set_gemm_path.argtypes = [ctypes.c_int]
     lib.hlq_set_gemv_path.restype = ctypes.c_int
     lib.hlq_set_gemv_path.argtypes = [ctypes.c_int]
+    lib.hlq_stream_read.restype = ctypes.c_int
+    lib.hlq_stream_read.argtypes = [vp, sz, ctypes.c_int, vp, sz, vp]
     lib.hlq_lut_gemm.restype = ctypes.c_int
     lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     return lib
@@ -201,6 +203,12 @@ def hlq_quantize(desc: HlqDesc, W, t_max: int = 10, with_err: bool = False, stre
     _check("hlq_quantize", lib.hlq_quantize(ctypes.byref(desc), _ptr(W), t_max, _ptr(codes), _ptr(scales), _ptr(zeros),
                                             _ptr(err) if with_err else None, _stream_ptr(stream)))
     return (codes, scales, zeros, err) if with_err else (codes, scales, zeros)
+
+
+def hlq_stream_read(src, nbytes: int, sink, blocks: int = 0, offset: int = 0, stream=None):
+    """Measurement helper: read nbytes of `src` (a cuda tensor) from byte `offset` on, once."""
+    _check("hlq_stream_read", lib.hlq_stream_read(_ptr(src) + offset, nbytes, blocks, _ptr(sink),
+                                                  sink.numel() * sink.element_size(), _stream_ptr(stream)))
 
 
 class GemvBatch:

@@ -245,7 +245,7 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
             const char *rec = tile_base[tn] + (size_t)w_ * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
-                const uint4 v = ((const uint4 *)rec)[j * w_ + lane_c[tn]];
+                const int4v v = __builtin_nontemporal_load((const int4v *)rec + (j * w_ + lane_c[tn]));   // read once: streaming (plane words only)
                 R.w[tn][j][0] = v.x; R.w[tn][j][1] = v.y; R.w[tn][j][2] = v.z; R.w[tn][j][3] = v.w;
             }
             const char *mrec = rec;

@@ -88,6 +88,18 @@ def test_host_side_argument_errors_launch_nothing():
     assert B.lib.hlq_lut_gemv(ctypes.byref(big), fake, fake, fake, 0, None, 0, None) == 1
 
 
+def test_stream_read_argument_errors_launch_nothing():
+    fake = 0x1000
+    assert B.lib.hlq_stream_read(None, 4096, 0, fake, 1 << 20, None) == 1
+    assert B.lib.hlq_stream_read(fake, 4096, 0, None, 1 << 20, None) == 1
+    assert B.lib.hlq_stream_read(fake + 8, 4096, 0, fake, 1 << 20, None) == 5
+    assert B.lib.hlq_stream_read(fake, 4100, 0, fake, 1 << 20, None) == 5
+    assert B.lib.hlq_stream_read(fake, 4096, -1, fake, 1 << 20, None) == 3
+    assert B.lib.hlq_stream_read(fake, 4096, 65537, fake, 1 << 20, None) == 3
+    assert B.lib.hlq_stream_read(fake, 1 << 20, 16, fake, 63, None) == 4
+    assert B.lib.hlq_stream_read(fake, 0, 0, fake, 0, None) == 0            # nothing to read
+
+
 def test_workspace_sizes_cover_every_path():
     # counters + room for split-K partial sums: K is never cut into slices shorter than four chunks,
     # so (K/128 + 3) // 4 slices of N fp32 values bound every GEMV plan; a few-rows GEMM needs that
