@@ -245,7 +245,8 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
             const char *rec = tile_base[tn] + (size_t)w_ * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
-                const int4v v = __builtin_nontemporal_load((const int4v *)rec + (j * w_ + lane_c[tn]));   // read once: streaming (plane words only)
+                // default cache policy: non-temporal loads, which help the matrix-core kernel, cost this one 2 us per layer
+                const int4v v = *((const int4v *)rec + (j * w_ + lane_c[tn]));
                 R.w[tn][j][0] = v.x; R.w[tn][j][1] = v.y; R.w[tn][j][2] = v.z; R.w[tn][j][3] = v.w;
             }
             const char *mrec = rec;
