@@ -164,28 +164,26 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     constexpr int RSTR = PERW / 4;                    // floats between wavefronts' sums
     const int M = BATCHED ? P.M : 1;
 
-    auto load_chunk = [&](int ch, Regs &R) {
-        // The lane offsets pass through an empty asm: they are re-extended to 64 bits at each use,
-        // which lets the loads take the form "scalar base + 32-bit lane offset" instead of one 64-bit
-        // vector add each.
-        asm volatile("" : "+v"(woff), "+v"(moff), "+v"(xoff));
-        const char *rec = tile_base + (size_t)tw * ((size_t)ch * Q * 16 + (size_t)hlq_groups_before(ch, G) * (Q + 1) * 2);
-#pragma unroll
-        for (int j = 0; j < Q; ++j) {
-            // plane words are read exactly once per call: streaming (non-temporal) loads, which measurably
-            // shorten the launch.  The 16-bit scale loads keep the default policy: a wavefront's 128-byte
-            // row reaches the L2 as several requests, and lines that are not kept there were counted as
-            // fetched from memory more than once (8 % more traffic per launch).  The activations, shared
-            // by all workgroups, stay cached as well.
-            const int4v v = __builtin_nontemporal_load((const int4v *)(rec + (size_t)(j * tw * 16) + woff));
-            R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
-        }
-        const char *mrec = rec;
-        if (G > 128) {   // the group's scales sit in the record of its first (even) chunk
-            const int c0 = ch & ~1;
-            mrec = tile_base + (size_t)tw * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
-        }
-        const char *m = mrec + (size_t)tw * Q * 16;
+    // Loads of one chunk, in two parts: the plane words (one 128-bit load per plane) and the rest (scales,
+    // zero points, activations).  The lane offsets pass through an empty asm: they are re-extended to
+    // 64 bits at each use, which lets the loads take the form "scalar base + 32-bit lane offset"
+    // instead of one 64-bit vector add each.
+    auto record_of = [&](int ch) -> const char * {
+        return tile_base + (size_t)tw * ((size_t)ch * Q * 16 + (size_t)hlq_groups_before(ch, G) * (Q + 1) * 2);
+    };
+    auto load_chunk_plane = [&](int ch, Regs &R, int j) {
+        asm volatile("" : "+v"(woff));
+        // plane words are read exactly once per call: streaming (non-temporal) loads, which measurably
+        // shorten the launch.  The 16-bit scale loads keep the default policy: a wavefront's 128-byte
+        // row reaches the L2 as several requests.  The activations, shared by all workgroups, stay
+        // cached as well.
+        const int4v v = __builtin_nontemporal_load((const int4v *)(record_of(ch) + (size_t)(j * tw * 16) + woff));
+        R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
+    };
+    auto load_chunk_rest = [&](int ch, Regs &R) {
+        asm volatile("" : "+v"(moff), "+v"(xoff));
+        // with G > 128 the group's scales sit in the record of its first (even) chunk
+        const char *m = record_of(G > 128 ? (ch & ~1) : ch) + (size_t)tw * Q * 16;
 #pragma unroll
         for (int sg = 0; sg < SEG; ++sg)
 #pragma unroll
@@ -194,6 +192,11 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
 #pragma unroll
         for (int m = 0; m < NROW; ++m)   // rows past M re-read the last row and are ignored
             R.x[m] = *(const uint32_t *)((const char *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)ch * 128) + xoff);
+    };
+    auto load_chunk = [&](int ch, Regs &R) {
+#pragma unroll
+        for (int j = 0; j < Q; ++j) load_chunk_plane(ch, R, j);
+        load_chunk_rest(ch, R);
     };
 
     // ---- scale: largest magnitude of the run's activations (as fp16 bit patterns) --------------------------
@@ -340,7 +343,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             load_chunk(ch_reload, R);
             return;
         }
-        constexpr int NI = 4 * Q;   // items; item n: column block n / Q, plane n % Q
+        constexpr int NI = 4 * Q;   // items; item n: plane n / 4, column block n % 4
         // result register s of an MFMA belongs to activation row s / SEG of the set and segment s % SEG
         auto apply = [&](int set, const float4v &d, int cb, int which) {
 #pragma unroll
@@ -365,9 +368,12 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             const uint2v t13 = __builtin_amdgcn_permlane32_swap(s01.y, s23.y, false, false);
             wt[j][0] = t02.x; wt[j][2] = t02.y; wt[j][1] = t13.x; wt[j][3] = t13.y;
         }
-        // this register set is free from here on (its scales and activations were consumed one chunk
-        // ahead): refill it now, before the MFMAs, so the next request is not held up by them
-        if (HLQ_MX_DEBUG != 2) load_chunk(ch_reload, R);
+        // This register set's scales and activations were consumed one chunk ahead: refill them now.
+        // The lane swaps above work in place, so a plane's registers hold its transposed words until its
+        // four items are done; they are reloaded right then (one load per plane, spread over the step)
+        // -- later than "as early as possible", but reloading everything here would cost a copy of
+        // every word (the loads would need the registers the swapped words sit in).
+        if (HLQ_MX_DEBUG != 2) load_chunk_rest(ch_reload, R);
         int8v B = expand(wt[0][0]);
         float4v d[NS][3];
         __builtin_amdgcn_sched_barrier(0);
@@ -377,11 +383,12 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             for (int set = 0; set < NS; ++set)
                 d[set][n % 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A[set], B, zero4, 1, 4, 0, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
-            if (n + 1 < NI) B = expand(wt[(n + 1) % Q][(n + 1) / Q]);
+            if (n + 1 < NI) B = expand(wt[(n + 1) / 4][(n + 1) % 4]);
+            if ((n + 1) % 4 == 0 && HLQ_MX_DEBUG != 2) load_chunk_plane(ch_reload, R, n / 4);
             if (n >= 1) {
 #pragma unroll
                 for (int set = 0; set < NS; ++set) {
-                    apply(set, d[set][(n - 1) % 3], (n - 1) / Q, (n - 1) % Q);
+                    apply(set, d[set][(n - 1) % 3], (n - 1) % 4, (n - 1) / 4);
                     // keeps all four result registers allocated up to here: if the unused ones were handed
                     // to the next operand while the MFMA is in flight, every write to them would have to
                     // wait for it
@@ -393,7 +400,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
         }
 #pragma unroll
         for (int set = 0; set < NS; ++set) {
-            apply(set, d[set][(NI - 1) % 3], (NI - 1) / Q, (NI - 1) % Q);
+            apply(set, d[set][(NI - 1) % 3], (NI - 1) % 4, (NI - 1) / 4);
 #pragma unroll
             for (int cb = 0; cb < 4; ++cb) apply(set, xs[set], cb, Q);
         }
