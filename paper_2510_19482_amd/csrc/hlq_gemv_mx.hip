@@ -169,7 +169,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     // 64 bits at each use, which lets the loads take the form "scalar base + 32-bit lane offset"
     // instead of one 64-bit vector add each.
     auto record_of = [&](int ch) -> const char * {
-        return tile_base + (size_t)tw * ((size_t)ch * Q * 16 + (size_t)hlq_groups_before(ch, G) * (Q + 1) * 2);
+        return tile_base + hlq_rec_in_tile(tw, ch, Q, G);
     };
     auto load_chunk_plane = [&](int ch, Regs &R, int j) {
         asm volatile("" : "+v"(woff));
@@ -187,8 +187,10 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
 #pragma unroll
         for (int sg = 0; sg < SEG; ++sg)
 #pragma unroll
-            for (int r = 0; r <= Q; ++r)
+            for (int r = 0; r <= Q; ++r) {
+                asm volatile("" : "+v"(moff));   // per load, or the compiler adds lane offset and base once, in vector registers
                 R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
+            }
 #pragma unroll
         for (int m = 0; m < NROW; ++m)   // rows past M re-read the last row and are ignored
             R.x[m] = *(const uint32_t *)((const char *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)ch * 128) + xoff);

@@ -59,12 +59,22 @@ struct HlqDims {
 __host__ __device__ __forceinline__ int hlq_bit_pos(int k0) { return (k0 >> 1) + 16 * (k0 & 1); }
 
 // groups whose meta is stored before chunk c of a tile
-__host__ __device__ __forceinline__ int hlq_groups_before(int c, int G) { return (c * HLQ_CHUNK_K + G - 1) / G; }
+// (c >= 0; written so that with a constant G it is one multiplication or one shift)
+__host__ __device__ __forceinline__ int hlq_groups_before(int c, int G)
+{
+    return G <= HLQ_CHUNK_K ? c * (HLQ_CHUNK_K / G) : (int)(((unsigned)c * HLQ_CHUNK_K + (unsigned)G - 1u) / (unsigned)G);
+}
 
 __host__ __device__ __forceinline__ int hlq_tile_width(int tile, int N)
 {
     const int w = N - tile * HLQ_TILE_N;
     return w < HLQ_TILE_N ? w : HLQ_TILE_N;
+}
+
+// byte offset of record c inside its tile; w = tile width.  Fits 32 bits: at most 64 columns x 2^14 chunks x 104 bytes.
+__host__ __device__ __forceinline__ uint32_t hlq_rec_in_tile(int w, int c, int q, int G)
+{
+    return (uint32_t)w * ((uint32_t)c * (uint32_t)(q * 16) + (uint32_t)hlq_groups_before(c, G) * (uint32_t)((q + 1) * 2));
 }
 
 // byte offset of record (tile, c); w = tile width
