@@ -59,14 +59,14 @@ hlq_gemm_lut_kernel(const char *__restrict__ packed, size_t col_bytes,
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u;
             const bool ok = col_ok && c < cend;
-            const char *rec = tile_base + (size_t)tw * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
+            const char *rec = tile_base + hlq_rec_in_tile(tw, c, Q, G);
 #pragma unroll
             for (int j = 0; j < Q; ++j)
                 w[u][j] = ok ? ((const uint4 *)rec)[j * tw + lane] : make_uint4(0u, 0u, 0u, 0u);
             const char *mrec = rec;
             if (G > 128) {   // the group's meta sits in the record of its first (even) chunk
                 const int ce = c & ~1;
-                mrec = tile_base + (size_t)tw * ((size_t)ce * Q * 16 + (size_t)hlq_groups_before(ce, G) * (Q + 1) * 2);
+                mrec = tile_base + hlq_rec_in_tile(tw, ce, Q, G);
             }
             const uint16_t *mp = (const uint16_t *)(mrec + (size_t)tw * Q * 16);
 #pragma unroll

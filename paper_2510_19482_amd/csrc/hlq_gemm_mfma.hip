@@ -91,7 +91,7 @@ __device__ __forceinline__ void gemm_mfma_block(const char *__restrict__ packed,
     const int cend = min(cbeg + cps, nchunks);
 
     auto load_w = [&](int c, Regs &R) {
-        const char *rec = tile_base + (size_t)tw * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
+        const char *rec = tile_base + hlq_rec_in_tile(tw, c, Q, G);
 #pragma unroll
         for (int j = 0; j < Q; ++j) {
             const uint4 v = ((const uint4 *)rec)[j * tw + lane_c];
@@ -100,7 +100,7 @@ __device__ __forceinline__ void gemm_mfma_block(const char *__restrict__ packed,
         const char *mrec = rec;
         if (G > 128) {
             const int c0 = c & ~1;
-            mrec = tile_base + (size_t)tw * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
+            mrec = tile_base + hlq_rec_in_tile(tw, c0, Q, G);
         }
         const uint16_t *m = (const uint16_t *)(mrec + (size_t)tw * Q * 16);
 #pragma unroll

@@ -242,7 +242,7 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
 #pragma unroll
         for (int tn = 0; tn < TN; ++tn) {
             const int w_ = tw[tn];
-            const char *rec = tile_base[tn] + (size_t)w_ * ((size_t)c * Q * 16 + (size_t)hlq_groups_before(c, G) * (Q + 1) * 2);
+            const char *rec = tile_base[tn] + hlq_rec_in_tile(w_, c, Q, G);
 #pragma unroll
             for (int j = 0; j < Q; ++j) {
                 // default cache policy: non-temporal loads, which help the matrix-core kernel, cost this one 2 us per layer
@@ -252,7 +252,7 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
             const char *mrec = rec;
             if (G > 128) {   // the group's meta sits in the record of its first (even) chunk
                 const int c0 = c & ~1;
-                mrec = tile_base[tn] + (size_t)w_ * ((size_t)c0 * Q * 16 + (size_t)hlq_groups_before(c0, G) * (Q + 1) * 2);
+                mrec = tile_base[tn] + hlq_rec_in_tile(w_, c0, Q, G);
             }
             const uint16_t *m = (const uint16_t *)(mrec + (size_t)w_ * Q * 16);
 #pragma unroll
