@@ -622,7 +622,7 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     hlq_status s;
     if (mx) {
         const int nsets = rows == 1 ? 0 : rows <= hlq_gemv_mx_rows_per_set(G) ? 1 : 2;
-        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, nsets, q, G, st);
+        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, nsets, rows, q, G, st);
         if (s != HLQ_OK) return s;
         return hlq_hip_status(hipGetLastError());
     }

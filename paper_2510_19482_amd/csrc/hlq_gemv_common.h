@@ -79,5 +79,5 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
 
 // matrix-core formulation (hlq_gemv_mx.hip): W (a power of two) wavefronts per workgroup, kw of them
 // per tile: ntg = ceil(ntiles / (W / kw)) tile groups, one arrival counter per TILE
-hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int q, int G, hipStream_t st);
+hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int rows, int q, int G, hipStream_t st);
 int hlq_gemv_mx_max_waves(int q, int G);

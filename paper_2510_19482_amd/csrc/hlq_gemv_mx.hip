@@ -117,12 +117,17 @@ constexpr int mx_nbuf(int, int) { return HLQ_MX_NBUF; }
 constexpr int mx_nbuf(int, int) { return 2; }
 #endif
 
-template <int Q, int G, int NS, bool BATCHED>
+// NR: activation rows the instantiation carries (0: the GEMV, one row per problem and no row stride);
+// NR <= NS * (rows per set).  Fewer rows than the sets could hold means fewer loads, conversions and
+// scale multiplications per chunk, so a launch picks the smallest instantiation that holds its M.
+template <int Q, int G, int NS, int NR>
 __global__ void __launch_bounds__(512)
 hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, const GemvProbs probs)
 {
     struct { int out_f32; } b = {out_f32_flag};
-    constexpr int NROW = mx_rows(G, NS, BATCHED);
+    constexpr bool BATCHED = NR > 0;
+    constexpr int NROW = BATCHED ? NR : 1;
+    static_assert(NROW <= mx_rows(G, NS, true), "more rows than the row sets hold");
     using Regs = MxRegs<Q, G, NROW>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
     constexpr int RPS = 4 / SEG;   // activation rows one operand can carry
@@ -477,26 +482,42 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
 }
 
 template <int Q, int G>
-void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int nsets, hipStream_t st)
+void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int nsets, int rows, hipStream_t st)
 {
     const dim3 blk(64 * W);
     const GemvKernelArgs a = gemv_kernel_args(b);
-    if (nsets == 0)
-        hlq_gemv_mx_kernel<Q, G, 1, false><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, 1), st>>>(a.lo, a.hi, a.out_f32, a.probs);
-    else if (nsets == 1)
-        hlq_gemv_mx_kernel<Q, G, 1, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 1, true)), st>>>(a.lo, a.hi, a.out_f32, a.probs);
-    else
-        hlq_gemv_mx_kernel<Q, G, 2, true><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, mx_rows(G, 2, true)), st>>>(a.lo, a.hi, a.out_f32, a.probs);
+    constexpr int RPS = mx_rows(G, 1, true);   // rows per set
+#define HLQ_MX_LAUNCH(NS_, NR_) \
+    hlq_gemv_mx_kernel<Q, G, NS_, NR_><<<nblocks, blk, (size_t)W * mx_wave_lds(Q, G, (NR_) > 0 ? (NR_) : 1), st>>>(a.lo, a.hi, a.out_f32, a.probs)
+    // the smallest instantiation that holds `rows` (rows <= nsets * RPS is checked by the caller)
+    if (nsets == 0) {
+        HLQ_MX_LAUNCH(1, 0);
+    } else if (nsets == 1) {
+        switch (rows < RPS ? rows : RPS) {
+        case 1: HLQ_MX_LAUNCH(1, 1); break;
+        case 2: HLQ_MX_LAUNCH(1, (RPS >= 2 ? 2 : RPS)); break;
+        case 3: HLQ_MX_LAUNCH(1, (RPS >= 3 ? 3 : RPS)); break;
+        default: HLQ_MX_LAUNCH(1, RPS); break;
+        }
+    } else {
+        switch (rows < 2 * RPS ? rows - RPS : RPS) {   // rows of the second set
+        case 1: HLQ_MX_LAUNCH(2, RPS + 1); break;
+        case 2: HLQ_MX_LAUNCH(2, (RPS >= 2 ? RPS + 2 : 2 * RPS)); break;
+        case 3: HLQ_MX_LAUNCH(2, (RPS >= 3 ? RPS + 3 : 2 * RPS)); break;
+        default: HLQ_MX_LAUNCH(2, 2 * RPS); break;
+        }
+    }
+#undef HLQ_MX_LAUNCH
 }
 
 template <int Q>
-hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, int nsets, hipStream_t st)
+hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, int nsets, int rows, hipStream_t st)
 {
     switch (G) {
-    case 32: launch_qg<Q, 32>(b, nblocks, W, nsets, st); return HLQ_OK;
-    case 64: launch_qg<Q, 64>(b, nblocks, W, nsets, st); return HLQ_OK;
-    case 128: launch_qg<Q, 128>(b, nblocks, W, nsets, st); return HLQ_OK;
-    case 256: launch_qg<Q, 256>(b, nblocks, W, nsets, st); return HLQ_OK;
+    case 32: launch_qg<Q, 32>(b, nblocks, W, nsets, rows, st); return HLQ_OK;
+    case 64: launch_qg<Q, 64>(b, nblocks, W, nsets, rows, st); return HLQ_OK;
+    case 128: launch_qg<Q, 128>(b, nblocks, W, nsets, rows, st); return HLQ_OK;
+    case 256: launch_qg<Q, 256>(b, nblocks, W, nsets, rows, st); return HLQ_OK;
     }
     return HLQ_ERR_UNSUPPORTED;
 }
@@ -508,14 +529,15 @@ int hlq_gemv_mx_rows_per_set(int G) { return mx_rows(G, 1, true); }
 
 // nsets: 0 = GEMV (one activation row per problem), 1 / 2 = batched rows with that many row sets
 // (every problem's M must fit nsets * hlq_gemv_mx_rows_per_set(G)).
-hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int q, int G, hipStream_t st)
+hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int rows, int q, int G, hipStream_t st)
 {
     if (W < 1 || W > 8 || (W & (W - 1)) || nsets < 0 || nsets > 2) return HLQ_ERR_UNSUPPORTED;
+    if (rows < 1 || rows > (nsets ? nsets : 1) * hlq_gemv_mx_rows_per_set(G)) return HLQ_ERR_UNSUPPORTED;
     switch (q) {
-    case 1: return launch_q<1>(G, b, nblocks, W, nsets, st);
-    case 2: return launch_q<2>(G, b, nblocks, W, nsets, st);
-    case 3: return launch_q<3>(G, b, nblocks, W, nsets, st);
-    case 4: return launch_q<4>(G, b, nblocks, W, nsets, st);
+    case 1: return launch_q<1>(G, b, nblocks, W, nsets, rows, st);
+    case 2: return launch_q<2>(G, b, nblocks, W, nsets, rows, st);
+    case 3: return launch_q<3>(G, b, nblocks, W, nsets, rows, st);
+    case 4: return launch_q<4>(G, b, nblocks, W, nsets, rows, st);
     }
     return HLQ_ERR_UNSUPPORTED;
 }

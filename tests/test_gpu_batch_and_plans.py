@@ -97,6 +97,7 @@ def test_one_workspace_serves_different_shapes():
 
 
 @pytest.mark.parametrize("M,q,G", [(2, 4, 128), (4, 2, 128), (8, 4, 128), (3, 3, 64), (2, 2, 32), (16, 2, 128), (5, 2, 64),
+                                   (3, 2, 128), (5, 3, 128), (6, 1, 256), (7, 4, 128), (4, 2, 64),   # every row count of the few-rows kernel
                                    (40, 3, 128), (130, 2, 128), (200, 4, 64), (257, 1, 32), (70, 2, 256)])
 def test_gemm_batch_equals_single_calls_and_oracle(M, q, G):
     # M within one pass of the few-rows kernel -> one grouped launch of the GEMV kernel; beyond it one
