@@ -51,6 +51,8 @@
 // gives lane l = c + 16 g word g (32 k) of column 16 cb + c for the four column blocks cb -- the
 // plane operand.  As result the lane holds, for column 16 cb + c, the dot products of term g
 // (register = segment).
+#include <type_traits>
+
 #include "hlq_gemv_common.h"
 
 #ifndef HLQ_MX_DEBUG
@@ -339,7 +341,8 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     // block cb), expands the plane word of item n+1 and applies the scales to the result of item
     // n-1; scheduling barriers keep the stages apart.  The LDS operands of the NEXT chunk are fetched
     // in the middle of the step.
-    auto step = [&](Regs &R, const Pre &p, const Regs &Rn, Pre &pn, int ch_reload) {
+    auto step = [&](auto reload_tag, Regs &R, const Pre &p, const Regs &Rn, Pre &pn, int ch_reload) {
+        constexpr bool reload = decltype(reload_tag)::value;   // false: nothing left to load into this register set
         if (HLQ_MX_DEBUG == 1) {   // timing experiment: loads only
             uint32_t m = 0;
 #pragma unroll
@@ -347,7 +350,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
 #pragma unroll
             for (int r = 0; r <= Q; ++r) m ^= R.mt[0][r];
             acc[0][0] += (float)m;
-            load_chunk(ch_reload, R);
+            if (reload) load_chunk(ch_reload, R);
             return;
         }
         constexpr int NI = 4 * Q;   // items; item n: plane n / 4, column block n % 4
@@ -380,7 +383,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
         // four items are done; they are reloaded right then (one load per plane, spread over the step)
         // -- later than "as early as possible", but reloading everything here would cost a copy of
         // every word (the loads would need the registers the swapped words sit in).
-        if (HLQ_MX_DEBUG != 2) load_chunk_rest(ch_reload, R);
+        if (HLQ_MX_DEBUG != 2 && reload) load_chunk_rest(ch_reload, R);
         int8v B = expand(wt[0][0]);
         float4v d[NS][3];
         __builtin_amdgcn_sched_barrier(0);
@@ -391,7 +394,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
                 d[set][n % 3] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(p.A[set], B, zero4, 1, 4, 0, 0, 0, 0);
             __builtin_amdgcn_sched_barrier(0);
             if (n + 1 < NI) B = expand(wt[(n + 1) / 4][(n + 1) % 4]);
-            if ((n + 1) % 4 == 0 && HLQ_MX_DEBUG != 2) load_chunk_plane(ch_reload, R, n / 4);
+            if ((n + 1) % 4 == 0 && HLQ_MX_DEBUG != 2 && reload) load_chunk_plane(ch_reload, R, n / 4);
             if (n >= 1) {
 #pragma unroll
                 for (int set = 0; set < NS; ++set) {
@@ -416,10 +419,28 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
     Pre pre[2];
     if (cbeg < cend && HLQ_MX_DEBUG != 1) prefetch(R[0], pre[0]);
-    for (int ch = cbeg; ch < cend; ch += NBUF) {
-#pragma unroll
-        for (int i = 0; i < NBUF; ++i) {
-            if (ch + i < cend) step(R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1], min(ch + i + NBUF, cend - 1));
+    static_assert(NBUF == 2, "the loop below alternates two register sets");
+    // Steps whose register set has a further chunk to fetch reload it; the last two of a run do not.  The
+    // choice is made between steps, at compile time inside them: a branch around the loads inside a step
+    // breaks its schedule and costs more than the loads it saves.
+    {
+        const std::true_type more;
+        const std::false_type last;
+        int ch = cbeg;
+        for (; ch + 3 < cend; ch += 2) {
+            step(more, R[0], pre[0], R[1], pre[1], ch + 2);
+            step(more, R[1], pre[1], R[0], pre[0], ch + 3);
+        }
+        const int left = cend - ch;   // 0 (empty run), 1, 2 or 3
+        if (left == 3) {
+            step(more, R[0], pre[0], R[1], pre[1], ch + 2);
+            step(last, R[1], pre[1], R[0], pre[0], 0);
+            step(last, R[0], pre[0], R[1], pre[1], 0);
+        } else if (left == 2) {
+            step(last, R[0], pre[0], R[1], pre[1], 0);
+            step(last, R[1], pre[1], R[0], pre[0], 0);
+        } else if (left == 1) {
+            step(last, R[0], pre[0], R[1], pre[1], 0);
         }
     }
 
