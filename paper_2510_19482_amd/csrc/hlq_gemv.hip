@@ -316,9 +316,8 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
     };
 
     // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
-    // Every iteration issues the same number of loads (past the end of the run the last chunk is
-    // simply read again and ignored), so the wait before each step can leave exactly the younger
-    // sets' loads outstanding.
+    // A register set is reloaded only while the run has a further chunk for it (the branch sits between
+    // steps, not inside one).
     if (cbeg < cend) {
         Regs R[NBUF];
 #pragma unroll
@@ -327,7 +326,7 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
 #pragma unroll
             for (int i = 0; i < NBUF; ++i) {
                 if (c + i < cend) step(R[i]);
-                if (HLQ_DEBUG_MODE != 2) load_chunk(min(c + i + NBUF, cend - 1), R[i]);
+                if (HLQ_DEBUG_MODE != 2 && c + i + NBUF < cend) load_chunk(c + i + NBUF, R[i]);
             }
         }
     }
