@@ -110,6 +110,11 @@ constexpr int mx_rows(int G, int NS, bool batched) { return batched ? NS * (4 / 
 // scales [64][stride] | sums [row][4][64] fp32
 constexpr int mx_xt_bytes(int nrow) { return nrow * 512 + 64; }
 constexpr int mx_wave_lds(int Q, int G, int nrow) { return mx_xt_bytes(nrow) + 64 * mx_meta_stride(Q, G) + nrow * 4 * 64 * 4; }
+// Instantiations whose chunk loop ends in steps without reloads (several copies of the step: they cost
+// registers).  The plain GEMV at one or two planes stays within 128 registers, i.e. two workgroups of
+// eight wavefronts per CU; the others would lose a resident workgroup or spill, which costs more than
+// re-reading the last chunk of a run twice.
+constexpr bool mx_peeled_tail(int Q, int G, int NR) { return NR == 0 && G >= 128 && Q <= 2; }
 // Register sets of chunk loads per wavefront (chunks in flight + 1).  Two: launches of this kernel
 // have thousands of wavefronts, which together keep far more than the bandwidth-delay product in
 // flight; deeper prefetch only costs registers, i.e. resident wavefronts (measured: 2 beats 3, 4, 6, 8).
@@ -419,13 +424,13 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     // ---- chunk loop: NBUF register sets, loads of the next NBUF-1 chunks in flight ----------------------
     Pre pre[2];
     if (cbeg < cend && HLQ_MX_DEBUG != 1) prefetch(R[0], pre[0]);
-    static_assert(NBUF == 2, "the loop below alternates two register sets");
-    // Steps whose register set has a further chunk to fetch reload it; the last two of a run do not.  The
-    // choice is made between steps, at compile time inside them: a branch around the loads inside a step
-    // breaks its schedule and costs more than the loads it saves.
-    {
-        const std::true_type more;
-        const std::false_type last;
+    static_assert(NBUF == 2, "the loops below alternate two register sets");
+    const std::true_type more;
+    const std::false_type last;
+    if constexpr (mx_peeled_tail(Q, G, NR)) {
+        // Steps whose register set has a further chunk to fetch reload it; the last two of a run do not.
+        // The choice is made between steps, at compile time inside them: a branch around the loads inside
+        // a step breaks its schedule and costs more than the loads it saves.
         int ch = cbeg;
         for (; ch + 3 < cend; ch += 2) {
             step(more, R[0], pre[0], R[1], pre[1], ch + 2);
@@ -441,6 +446,14 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             step(last, R[1], pre[1], R[0], pre[0], 0);
         } else if (left == 1) {
             step(last, R[0], pre[0], R[1], pre[1], 0);
+        }
+    } else {
+        // every step reloads; past the end of the run the last chunk is read again and ignored
+        for (int ch = cbeg; ch < cend; ch += NBUF) {
+#pragma unroll
+            for (int i = 0; i < NBUF; ++i) {
+                if (ch + i < cend) step(more, R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1], min(ch + i + NBUF, cend - 1));
+            }
         }
     }
 
