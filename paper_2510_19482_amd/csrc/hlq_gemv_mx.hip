@@ -112,8 +112,9 @@ constexpr int mx_xt_bytes(int nrow) { return nrow * 512 + 64; }
 constexpr int mx_wave_lds(int Q, int G, int nrow) { return mx_xt_bytes(nrow) + 64 * mx_meta_stride(Q, G) + nrow * 4 * 64 * 4; }
 // Instantiations whose chunk loop ends in steps without reloads (several copies of the step: they cost
 // registers).  The plain GEMV at one or two planes stays within 128 registers, i.e. two workgroups of
-// eight wavefronts per CU; the others would lose a resident workgroup or spill, which costs more than
-// re-reading the last chunk of a run twice.
+// eight wavefronts per CU; the others would lose a resident workgroup or spill, so they drop the loads
+// past the end of a run through the range check of a buffer descriptor instead (measured a few per
+// cent slower than the peeled loop where both are possible: a dropped load still takes its issue slot).
 constexpr bool mx_peeled_tail(int Q, int G, int NR) { return NR == 0 && G >= 128 && Q <= 2; }
 // Register sets of chunk loads per wavefront (chunks in flight + 1).  Two: launches of this kernel
 // have thousands of wavefronts, which together keep far more than the bandwidth-delay product in
@@ -177,35 +178,55 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     const int M = BATCHED ? P.M : 1;
 
     // Loads of one chunk, in two parts: the plane words (one 128-bit load per plane) and the rest (scales,
-    // zero points, activations).  The lane offsets pass through an empty asm: they are re-extended to
-    // 64 bits at each use, which lets the loads take the form "scalar base + 32-bit lane offset"
-    // instead of one 64-bit vector add each.
+    // zero points, activations).  Two forms of the weight loads:
+    //  * PEELED instantiations (their chunk loop ends in steps without loads): plain loads.  The lane
+    //    offsets pass through an empty asm: they are re-extended to 64 bits at each use, which lets the
+    //    loads take the form "scalar base + 32-bit lane offset" instead of one 64-bit vector add each.
+    //  * the others, whose every step asks for "the chunk two ahead": loads through a buffer descriptor
+    //    over this wavefront's part of the tile, [tile_base, first byte after the run's last record).
+    //    The hardware's range check returns zero for anything beyond it without touching memory, so
+    //    past the end of a run nothing is fetched -- no branch, no clamping.
+    // Plane words are read exactly once per call: streaming (non-temporal) loads, which measurably
+    // shorten the launch.  The 16-bit scale loads keep the default policy: a wavefront's 128-byte row
+    // reaches the L2 as several requests.  The activations, shared by all workgroups, stay cached.
+    constexpr bool PEELED = mx_peeled_tail(Q, G, NR);
+    const uint32_t run_end = (!PEELED && tile_ok) ? hlq_rec_in_tile(tw, cend, Q, G) : 0u;
+    const __amdgpu_buffer_rsrc_t wrsrc = __builtin_amdgcn_make_buffer_rsrc((void *)tile_base, 0, (int)run_end, 0x00020000);
     auto record_of = [&](int ch) -> const char * {
         return tile_base + hlq_rec_in_tile(tw, ch, Q, G);
     };
     auto load_chunk_plane = [&](int ch, Regs &R, int j) {
-        asm volatile("" : "+v"(woff));
-        // plane words are read exactly once per call: streaming (non-temporal) loads, which measurably
-        // shorten the launch.  The 16-bit scale loads keep the default policy: a wavefront's 128-byte
-        // row reaches the L2 as several requests.  The activations, shared by all workgroups, stay
-        // cached as well.
-        const int4v v = __builtin_nontemporal_load((const int4v *)(record_of(ch) + (size_t)(j * tw * 16) + woff));
+        int4v v;
+        if constexpr (PEELED) {
+            asm volatile("" : "+v"(woff));
+            v = __builtin_nontemporal_load((const int4v *)(record_of(ch) + (size_t)(j * tw * 16) + woff));
+        } else {
+            const uint32_t so = hlq_rec_in_tile(tw, ch, Q, G) + (uint32_t)(j * tw * 16);
+            v = __builtin_bit_cast(int4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)woff, (int)so, 2));   // aux 2: non-temporal
+        }
         R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
     };
     auto load_chunk_rest = [&](int ch, Regs &R) {
         asm volatile("" : "+v"(moff), "+v"(xoff));
         // with G > 128 the group's scales sit in the record of its first (even) chunk
-        const char *m = record_of(G > 128 ? (ch & ~1) : ch) + (size_t)tw * Q * 16;
+        const int cm = G > 128 ? (ch & ~1) : ch;
 #pragma unroll
         for (int sg = 0; sg < SEG; ++sg)
 #pragma unroll
             for (int r = 0; r <= Q; ++r) {
-                asm volatile("" : "+v"(moff));   // per load, or the compiler adds lane offset and base once, in vector registers
-                R.mt[sg][r] = *(const uint16_t *)(m + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
+                if constexpr (PEELED) {
+                    asm volatile("" : "+v"(moff));   // per load, or the compiler adds lane offset and base once, in vector registers
+                    R.mt[sg][r] = *(const uint16_t *)(record_of(cm) + (size_t)tw * Q * 16 + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
+                } else {
+                    const uint32_t mo = hlq_rec_in_tile(tw, cm, Q, G) + (uint32_t)(tw * Q * 16 + (sg * (Q + 1) + r) * tw * 2);
+                    R.mt[sg][r] = __builtin_amdgcn_raw_buffer_load_b16(wrsrc, (int)moff, (int)mo, 0);
+                }
             }
+        // activations: plain loads; the chunk index stays inside the run (rows past M re-read the last row and are ignored)
+        const int chx = PEELED ? ch : max(min(ch, cend - 1), sbeg);
 #pragma unroll
-        for (int m = 0; m < NROW; ++m)   // rows past M re-read the last row and are ignored
-            R.x[m] = *(const uint32_t *)((const char *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)ch * 128) + xoff);
+        for (int m = 0; m < NROW; ++m)
+            R.x[m] = *(const uint32_t *)((const char *)(P.x + (size_t)min(m, M - 1) * P.ldx + (size_t)chx * 128) + xoff);
     };
     auto load_chunk = [&](int ch, Regs &R) {
 #pragma unroll
@@ -226,10 +247,11 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             xu[m][i] = xr[(size_t)max(min(i, nrun - 1), 0) * 64];
     }
 
-    // weight loads of the first chunks (an empty run re-reads the slice's first chunk and drops it)
+    // weight loads of the first chunks (an empty run re-reads the slice's first chunk and drops it, or
+    // gets zeros from the range check)
     Regs R[NBUF];
 #pragma unroll
-    for (int i = 0; i < NBUF; ++i) load_chunk(max(min(cbeg + i, cend - 1), sbeg), R[i]);
+    for (int i = 0; i < NBUF; ++i) load_chunk(PEELED ? max(min(cbeg + i, cend - 1), sbeg) : cbeg + i, R[i]);
 
     // with the first loads on their way: clear the operand area (rows past M are never converted, their
     // codes stay zero)
@@ -427,7 +449,7 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     static_assert(NBUF == 2, "the loops below alternate two register sets");
     const std::true_type more;
     const std::false_type last;
-    if constexpr (mx_peeled_tail(Q, G, NR)) {
+    if constexpr (PEELED) {
         // Steps whose register set has a further chunk to fetch reload it; the last two of a run do not.
         // The choice is made between steps, at compile time inside them: a branch around the loads inside
         // a step breaks its schedule and costs more than the loads it saves.
@@ -448,11 +470,11 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             step(last, R[0], pre[0], R[1], pre[1], 0);
         }
     } else {
-        // every step reloads; past the end of the run the last chunk is read again and ignored
+        // every step asks for the chunk NBUF ahead; past the end of the run the range check answers with zeros
         for (int ch = cbeg; ch < cend; ch += NBUF) {
 #pragma unroll
             for (int i = 0; i < NBUF; ++i) {
-                if (ch + i < cend) step(more, R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1], min(ch + i + NBUF, cend - 1));
+                if (ch + i < cend) step(more, R[i], pre[i & 1], R[(i + 1) % NBUF], pre[(i + 1) & 1], ch + i + NBUF);
             }
         }
     }
