@@ -105,3 +105,32 @@ def test_config4_prefill_whole_layer_one_grouped_launch():
         assert err.max() <= TOL, s.name
     del packs, Xs, Ys
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("M", [2, 5, 8, 16])
+def test_config3_small_batch_whole_layer_one_grouped_launch(M):
+    # configuration 3 in the launch the small-batch figures are quoted on: the seven matrices of the 8B layer,
+    # q = 4, in one hlq_lut_gemm_batch call (few-rows kernel with one and two row sets up to M = 8, tiled kernel
+    # above), every output column against the C oracle
+    from paper_2510_19482_amd import binding as B
+    from gpu_util import dev
+    q, G = 4, 128
+    shapes = synth.LLAMA31_8B_LAYER
+    descs, packs, Xs, Ys, refs = [], [], [], [], []
+    for s in shapes:
+        say("config cfg3 grouped", s.name, s.K, s.N, "M", M)
+        codes, S, Z = synth.make_weight(s.K, s.N, q, G, "cfg3g", s.name)
+        X = synth.make_x(M, s.K, "cfg3g", s.name, M, outliers=True)
+        d, p = pack_on_gpu(codes, S, Z, q, G)
+        refs.append(c_oracle.gemm_f64(X, codes, S, Z, q, G))
+        descs.append(d); packs.append(p); Xs.append(dev(X))
+        Ys.append(torch.empty((M, s.N), dtype=torch.float16, device="cuda"))
+        del codes, S, Z, X
+    B.GemmBatch(descs, packs, Xs, Ys).launch()
+    torch.cuda.synchronize()
+    for s, Y, ref in zip(shapes, Ys, refs):
+        err = O.row_rel_err(Y.float().cpu().numpy().astype(np.float64), ref)
+        say("   ", s.name, "max row err", float(err.max()))
+        assert err.max() <= TOL, s.name
+    del packs, Xs, Ys
+    torch.cuda.empty_cache()
