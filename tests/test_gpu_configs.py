@@ -134,3 +134,36 @@ def test_config3_small_batch_whole_layer_one_grouped_launch(M):
         assert err.max() <= TOL, s.name
     del packs, Xs, Ys
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("q", [2, 3])
+@pytest.mark.parametrize("path", ["matrix cores", "lookups"])
+def test_config2_whole_layer_one_grouped_launch(q, path):
+    # the launch bench.py times: the seven GEMVs of the 8B layer in one hlq_lut_gemv_batch call, both
+    # formulations, every output against the C oracle
+    from paper_2510_19482_amd import binding as B
+    from gpu_util import dev
+    G = 128
+    shapes = synth.LLAMA31_8B_LAYER
+    descs, packs, xs, ys, refs = [], [], [], [], []
+    for s in shapes:
+        say("config cfg2 grouped", path, s.name, s.K, s.N, "q", q)
+        codes, S, Z = synth.make_weight(s.K, s.N, q, G, "cfg2g", s.name)
+        X = synth.make_x(1, s.K, "cfg2g", s.name)
+        d, p = pack_on_gpu(codes, S, Z, q, G)
+        refs.append(c_oracle.gemm_f64(X, codes, S, Z, q, G))
+        descs.append(d); packs.append(p); xs.append(dev(X[0]))
+        ys.append(torch.empty(s.N, dtype=torch.float16, device="cuda"))
+        del codes, S, Z
+    B.set_gemv_path(B.GEMV_LUT if path == "lookups" else B.GEMV_MX)
+    try:
+        B.GemvBatch(descs, packs, xs, ys).launch()
+        torch.cuda.synchronize()
+    finally:
+        B.set_gemv_path(B.GEMV_AUTO)
+    for s, y, ref in zip(shapes, ys, refs):
+        err = O.row_rel_err(y.float().cpu().numpy().astype(np.float64)[None, :], ref)
+        say("   ", s.name, "max row err", float(err.max()))
+        assert err.max() <= TOL, s.name
+    del packs, xs, ys
+    torch.cuda.empty_cache()
