@@ -86,10 +86,18 @@ HLQ_API hlq_status hlq_workspace_bytes(const hlq_desc *d, int64_t M, size_t *byt
 /* Workspace size for hlq_lut_gemv_batch over `count` descriptors (host array). */
 HLQ_API hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, size_t *bytes);
 
-/* Zero the arrival counters of a freshly allocated workspace (asynchronous on `stream`). */
+/* Zero the arrival counters of a freshly allocated workspace (asynchronous on `stream`).
+ * REQUIRED once per workspace before its first use.  The kernels cannot tell a counter that was
+ * never cleared from one that counts arrivals: with K split across workgroups, a workgroup adds the
+ * partial sums when the counter of its column tile reaches (slices - 1), so on memory that does not
+ * start at zero that moment never comes, or comes early: the affected outputs are then not written
+ * at all (they keep what y held) or are sums over the slices that happened to be there.  No fault, no
+ * error code -- wrong numbers.  Launches whose plan does not split K across workgroups do not
+ * touch the workspace. */
 HLQ_API hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream);
 
-/* Alg. 1, Sec. 3.2 (alternating optimisation for HLQ): quantizes W[K, N] group by group (G
+/* Alg. 1 (Sec. 4.1; its steps "Bit-Pattern Selection" and "Linear Reconstruction" are defined in
+ * Sec. 4.2), the alternating optimisation for HLQ: quantizes W[K, N] group by group (G
  * consecutive k of a column) into the tensors hlq_pack consumes.  Start: uniform grid over the
  * group's [min, max]; then t_max times (the paper uses 10): per weight the nearest of the 2^q
  * values sum_j s_j bit_j(c) + z (ties: smallest code), then (s, z) by least squares given the
@@ -121,7 +129,8 @@ HLQ_API hlq_status hlq_pack(const hlq_desc *d, const uint8_t *codes, const uint1
 HLQ_API hlq_status hlq_unpack(const hlq_desc *d, const void *packed, uint8_t *codes,
                       uint16_t *scales, uint16_t *zeros, void *stream);
 
-/* y[N] = x[K] @ W^  (M = 1 decode; Sec. 2, Eq. 5-6: per plane and quant group the dot product
+/* y[N] = x[K] @ W^  (M = 1 decode; Sec. 2 "Bit-Serial LUT-Based GEMM" and App. B on weights in the format
+ * of Eq. 3: per plane and quant group the dot product
  * <b_j, x>, times s_j, plus z times the group's activation sum).  The per-plane dot products are
  * taken either on the matrix cores (default) or with the 16-entry tables of App. B, see
  * hlq_set_gemv_path; W^ is never formed.
@@ -158,14 +167,33 @@ HLQ_API hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const vo
                                       const int64_t *ldy, hlq_out_dtype out, void *ws, size_t ws_bytes,
                                       void *stream);
 
-/* Tuning knob (process-wide, not thread-safe; for benchmarks and tests): force the launch shape
+/* Tuning knob (process-wide; for benchmarks and tests.  Each of the knobs below is one atomic value:
+ * setting it while another thread launches is safe, and that launch uses the old or the new value;
+ * there is no per-call or per-thread setting): force the launch shape
  * of the GEMV kernel -- column tiles per wavefront (1 or 2), wavefronts per workgroup (1..16),
  * chunks of 128 k per wavefront -- instead of the built-in choice.  0 leaves a value automatic.
  * Results stay within the documented tolerance for every setting; only speed changes.
  * Values outside the ranges above: HLQ_ERR_UNSUPPORTED. */
 HLQ_API hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int chunks_per_wave);
 
-/* Tuning knob (process-wide, not thread-safe): formulation of the per-plane dot products in
+/* Host-only: the work split hlq_lut_gemv_batch (M = 1) or the few-rows launch of hlq_lut_gemm_batch
+ * (2 <= M <= rows one pass carries) would use for these `count` problems with the knobs as they
+ * are now; nothing is launched and no GPU is needed.  For tests and tools: every K slice of a
+ * plan starts inside K, i.e. (slices - 1) * chunks_per_slice < K / 128.
+ *   descs host array of `count` (1..8) descriptors sharing q and G; out host array of `count`.
+ * M outside what the few-rows kernel carries: HLQ_ERR_UNSUPPORTED. */
+typedef struct {
+    int32_t formulation;          /* 1 = table lookups, 2 = matrix cores                             */
+    int32_t waves_per_workgroup;  /* wavefronts of a workgroup                                       */
+    int32_t waves_per_tile;       /* of those, the wavefronts that share one column tile's K slice   */
+    int32_t chunks_per_slice;     /* chunks of 128 k per K slice (a slice = one workgroup's share)   */
+    int32_t slices;               /* K slices, i.e. partial sums per output in the workspace         */
+    int32_t tile_groups;          /* groups of column tiles, one workgroup per (group, slice)        */
+    int32_t first_block, blocks;  /* this problem's range of workgroups in the launch                */
+} hlq_gemv_plan_info;
+HLQ_API hlq_status hlq_gemv_plan_query(int count, const hlq_desc *descs, int64_t M, hlq_gemv_plan_info *out);
+
+/* Tuning knob (process-wide, atomic): formulation of the per-plane dot products in
  * hlq_lut_gemv / hlq_lut_gemv_batch.  0 = automatic, 1 = table lookups (App. B), 2 = matrix
  * cores (plane words expanded to 4-bit floats, activations as an exact sum of four 8-bit
  * floats; the matrix core keeps 13 bits below the largest product of an 8-element run, so a
@@ -173,7 +201,7 @@ HLQ_API hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup
  * Other values: HLQ_ERR_UNSUPPORTED.  Activations must be finite. */
 HLQ_API hlq_status hlq_set_gemv_path(int path);
 
-/* Tuning knob (process-wide, not thread-safe): formulation used by hlq_lut_gemm for M > 1.
+/* Tuning knob (process-wide, atomic): formulation used by hlq_lut_gemm for M > 1.
  * 0 = automatic (matrix cores from M = 2 on, the measured crossover),
  * 1 = table lookups always,
  * 2 = matrix cores always: for a few rows (M <= 4 at G >= 128, <= 2 at G = 64, 1 at G = 32) the

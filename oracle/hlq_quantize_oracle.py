@@ -1,4 +1,4 @@
-"""CPU oracle for the HLQ quantizer (Alg. 1, Sec. 3.2 "Weight Error Reduction via Hierarchical Linear
+"""CPU oracle for the HLQ quantizer (Alg. 1 in Sec. 4.1; Sec. 4.2 "Weight Error Reduction via Hierarchical Linear
 Quantization").  TEST INFRASTRUCTURE ONLY: only tests and the smoke check may import this module;
 it shares no code with the HIP library.
 
@@ -9,8 +9,8 @@ order and notation, in fp64:
     Delta = (max - min) / (2^q - 1); s = [Delta, 2 Delta, ...]; z = min  (steps 2-3)
     C = all 2^q binary combinations, C[c, j] = bit j of c                (step 4)
     repeat T_max times:
-        W^ = W~ - z;  V = s C^T;  c* = argmin_c |W^ - V_c|;  B = C[c*]   (steps 6-9, Eq. 9)
-        (s, z) = LSE(W~, B)                                              (step 10, Eq. 10-11)
+        W^ = W~ - z;  V = s C^T;  c* = argmin_c |W^ - V_c|;  B = C[c*]   (steps 6-9, Bit-Pattern Selection)
+        (s, z) = LSE(W~, B)                                              (step 10, Linear Reconstruction / LSE)
 
 Plane j of the result is bit j of the code and belongs to s_j (initially 2^j Delta), the same
 convention hlq_pack uses.  Readings where the paper is silent:
@@ -27,7 +27,7 @@ Pins (tests/test_oracle_quantize.py): the first bit-pattern selection equals tex
 round-to-nearest; the objective never increases (each half-step is a minimisation); the LSE step
 equals numpy.linalg.lstsq on full-rank groups and the two-cluster means for q = 1; brute force
 over all bit assignments on tiny groups bounds it from below; on Gaussian weights the final error
-is well below round-to-nearest (Fig. 3's qualitative claim); degenerate groups.
+is well below round-to-nearest (the qualitative claim of the weight-distribution / MSE figure of Sec. 3); degenerate groups.
 """
 from __future__ import annotations
 
@@ -60,7 +60,7 @@ def init_params(Wg: np.ndarray, q: int):
 
 
 def select_bits(Wg: np.ndarray, s: np.ndarray, z: np.ndarray, q: int) -> np.ndarray:
-    """Bit-pattern selection (Eq. 9): per weight the combination whose value is nearest."""
+    """Bit-pattern selection (Sec. 4.2, Bit-Pattern Selection; Eq. 5): per weight the combination whose value is nearest."""
     C = combinations(q)
     V = s @ C.T                                          # [groups, 2^q]
     What = Wg - z[:, None]
@@ -102,7 +102,7 @@ def independent_columns(A_int: np.ndarray):
 
 
 def lse(Wg: np.ndarray, codes_g: np.ndarray, s_prev: np.ndarray, z_prev: np.ndarray, q: int):
-    """Linear reconstruction (Eq. 10): least squares for (z, s_0, ..., s_{q-1}) given the bits, group by
+    """Linear reconstruction (Sec. 4.2, Linear Reconstruction: the LSE step): least squares for (z, s_0, ..., s_{q-1}) given the bits, group by
     group.  Unknowns of dependent columns keep their previous values (see the module header)."""
     ng, G = Wg.shape
     s, z = s_prev.copy(), z_prev.copy()
@@ -151,7 +151,7 @@ def quantize(W: np.ndarray, q: int, G: int, t_max: int = 10, history: bool = Fal
 
 
 def rtn_uniform(W: np.ndarray, q: int, G: int):
-    """Textbook asymmetric round-to-nearest on a uniform grid (the comparison quantizer of Fig. 3):
+    """Textbook asymmetric round-to-nearest on a uniform grid (the comparison quantizer of the MSE figure of Sec. 3):
     code = clip(round((w - min) / Delta)), W^ = Delta * code + min.  Independent of the functions above."""
     K, N = W.shape
     Wg = np.asarray(W, dtype=np.float64).reshape(K // G, G, N)

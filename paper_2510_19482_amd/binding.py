@@ -21,6 +21,11 @@ class HlqDesc(ctypes.Structure):
                 ("G", ctypes.c_int32), ("layout", ctypes.c_uint32)]
 
 
+class GemvPlanInfo(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("formulation", "waves_per_workgroup", "waves_per_tile", "chunks_per_slice",
+                                              "slices", "tile_groups", "first_block", "blocks")]
+
+
 class HlqError(RuntimeError):
     def __init__(self, fn: str, status: int):
         self.status = status
@@ -70,6 +75,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_lut_gemv_batch.restype = ctypes.c_int
     lib.hlq_lut_gemv_batch.argtypes = [ctypes.c_int, dp, ctypes.POINTER(vp), ctypes.POINTER(vp),
                                        ctypes.POINTER(vp), ctypes.c_int, vp, sz, vp]
+    lib.hlq_gemv_plan_query.restype = ctypes.c_int
+    lib.hlq_gemv_plan_query.argtypes = [ctypes.c_int, dp, i64, ctypes.POINTER(GemvPlanInfo)]
     lib.hlq_set_gemv_plan.restype = ctypes.c_int
     lib.hlq_set_gemv_plan.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.hlq_set_gemm_path.restype = ctypes.c_int
@@ -105,6 +112,15 @@ def _check(fn: str, status: int) -> None:
 
 def set_gemv_plan(tiles_per_wave: int = 0, waves_per_workgroup: int = 0, chunks_per_wave: int = 0) -> None:
     _check("hlq_set_gemv_plan", lib.hlq_set_gemv_plan(tiles_per_wave, waves_per_workgroup, chunks_per_wave))
+
+
+def gemv_plan_query(descs, M: int = 1):
+    """Work split of a grouped GEMV / few-rows launch over `descs` (host arithmetic, no GPU needed)."""
+    n = len(descs)
+    arr = (HlqDesc * n)(*descs)
+    out = (GemvPlanInfo * n)()
+    _check("hlq_gemv_plan_query", lib.hlq_gemv_plan_query(n, arr, M, out))
+    return list(out)
 
 
 GEMM_AUTO, GEMM_LUT, GEMM_MFMA, GEMM_MFMA_FP16 = 0, 1, 2, 3

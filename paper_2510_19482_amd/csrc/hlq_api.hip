@@ -134,6 +134,20 @@ hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int ch
     return hlq_gemv_plan_override(tiles_per_wave, waves_per_workgroup, chunks_per_wave);
 }
 
+hlq_status hlq_gemv_plan_query(int count, const hlq_desc *descs, int64_t M, hlq_gemv_plan_info *out)
+{
+    if (!descs || !out) return HLQ_ERR_NULL;
+    if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
+    if (M < 1 || M > 64) return HLQ_ERR_UNSUPPORTED;
+    HlqDims dms[HLQ_MAX_BATCH];
+    for (int i = 0; i < count; ++i) {
+        hlq_status s = hlq_check_desc(&descs[i], &dms[i]);
+        if (s != HLQ_OK) return s;
+        if (descs[i].q != descs[0].q || descs[i].G != descs[0].G) return HLQ_ERR_UNSUPPORTED;
+    }
+    return hlq_gemv_plan_describe(count, dms, (int)M, out);
+}
+
 hlq_status hlq_set_gemm_path(int path) { return hlq_gemm_path_override(path); }
 
 hlq_status hlq_set_gemv_path(int path) { return hlq_gemv_path_override(path); }

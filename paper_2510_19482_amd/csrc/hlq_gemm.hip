@@ -5,6 +5,8 @@
 // U = 2 chunks (256 k).  Table entries of the MB rows are interleaved, T[t][i][r], so one LDS
 // read of MB floats serves all rows for a decoded 4-bit slice: the weight words are loaded
 // and decoded once per step and shared by the rows, as in the batched reading of App. B.
+#include <atomic>
+
 #include "hlq_internal.h"
 
 namespace {
@@ -249,7 +251,7 @@ hlq_status hlq_launch_gemm_lut(const HlqDims &dm, const void *packed, const uint
 
 // ---- formulation choice ---------------------------------------------------------------------------
 // 0 = automatic (by M), 1 = table lookups (this file), 2 = matrix cores (hlq_gemm_mfma.hip)
-static int g_gemm_path = 0;
+static std::atomic<int> g_gemm_path{0};
 
 hlq_status hlq_gemm_path_override(int path)
 {
@@ -260,15 +262,16 @@ hlq_status hlq_gemm_path_override(int path)
 
 static bool use_mfma(int64_t M)
 {
-    if (g_gemm_path == 1) return false;
-    if (g_gemm_path >= 2) return true;
+    const int path = g_gemm_path.load(std::memory_order_relaxed);
+    if (path == 1) return false;
+    if (path >= 2) return true;
     // measured on MI355X (8B shapes, q = 2..4, HIP-graph timing): the matrix-core kernels are faster
     // than the lookup kernel from M = 2 on, and the gap grows with M
     return M >= 2;
 }
 
 // true if hlq_launch_gemm sends M rows (that fit one pass) to the few-rows matrix-core GEMV kernel
-bool hlq_gemm_uses_mx_rows(int64_t M) { return use_mfma(M) && g_gemm_path != 3; }
+bool hlq_gemm_uses_mx_rows(int64_t M) { return use_mfma(M) && g_gemm_path.load(std::memory_order_relaxed) != 3; }
 
 // true if hlq_launch_gemm computes M rows on the matrix cores (either kernel)
 bool hlq_gemm_uses_matrix_cores(int64_t M) { return use_mfma(M); }
@@ -290,7 +293,7 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
         // up to one row set of the matrix-core GEMV kernel (several activation rows per operand): measured
         // faster than the tiled kernel there; from the second row set on the tiled kernel, whose time
         // hardly depends on M up to 32 rows, is as fast or faster for a single call
-        if (g_gemm_path != 3 && M <= hlq_gemv_mx_rows_per_set(dm.G))
+        if (g_gemm_path.load(std::memory_order_relaxed) != 3 && M <= hlq_gemv_mx_rows_per_set(dm.G))
             return hlq_launch_gemm_mx_rows(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
         return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
     }

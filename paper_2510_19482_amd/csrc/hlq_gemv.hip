@@ -26,6 +26,8 @@
 // the partials in slice order, so the result does not depend on arrival order.
 #include <stdlib.h>
 
+#include <atomic>
+
 #include "hlq_gemv_common.h"
 
 namespace {
@@ -208,7 +210,8 @@ hlq_gemv_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, co
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     // this wavefront's run of chunks: the slice is cut into W near-equal parts
-    const int sbeg = slice * P.cps;
+    // (the host plans every slice to start inside K; the clamp keeps every address inside the tile and x)
+    const int sbeg = min(slice * P.cps, P.nchunks - 1);
     const int send = min(sbeg + P.cps, P.nchunks);
     const int len = send - sbeg;
     const int cbeg = sbeg + (len * wave) / W;
@@ -431,15 +434,18 @@ struct GemvPlan {
     int cpw;   // target chunks per wavefront; a slice is W * cpw chunks (rounded to even)
 };
 
-// process-wide overrides set by hlq_set_gemv_plan (0 = automatic)
-int g_plan_tn = 0, g_plan_w = 0, g_plan_cpw = 0;
+// process-wide overrides set by hlq_set_gemv_plan (0 = automatic).  Atomic, so that a launch on one
+// thread reads a whole value while another thread sets a knob; a launch that overlaps a change of the
+// three plan values may still see some old and some new ones (each combination is a valid plan).
+std::atomic<int> g_plan_tn{0}, g_plan_w{0}, g_plan_cpw{0};
 // formulation: 0 automatic, 1 table lookup, 2 matrix core (hlq_set_gemv_path)
-int g_gemv_path = 0;
+std::atomic<int> g_gemv_path{0};
 
 bool use_mx()
 {
     static const int env_path = env_int("HLQ_GEMV_PATH", 0);
-    const int path = g_gemv_path ? g_gemv_path : env_path;
+    const int knob = g_gemv_path.load(std::memory_order_relaxed);
+    const int path = knob ? knob : env_path;
     return path != 1;   // automatic: the matrix-core kernel is the faster one on every measured shape
 }
 
@@ -464,9 +470,9 @@ GemvPlan plan_gemv(long units)
     if (env_tn) pl.TN = env_tn;
     if (env_w) pl.W = env_w;
     if (env_cpw) pl.cpw = env_cpw;
-    if (g_plan_tn) pl.TN = g_plan_tn;
-    if (g_plan_w) pl.W = g_plan_w;
-    if (g_plan_cpw) pl.cpw = g_plan_cpw;
+    if (const int v = g_plan_tn.load(std::memory_order_relaxed)) pl.TN = v;
+    if (const int v = g_plan_w.load(std::memory_order_relaxed)) pl.W = v;
+    if (const int v = g_plan_cpw.load(std::memory_order_relaxed)) pl.cpw = v;
     return pl;
 }
 
@@ -488,6 +494,9 @@ void plan_mx_problem(const HlqDims &dm, int W, int cpw, GemvProb &p)
     const int tiles_per_wg = W / p.kw;
     p.ntg = (dm.ntiles + tiles_per_wg - 1) / tiles_per_wg;
     p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
+    // rounding the slice length up can leave trailing slices without a chunk: count the slices again, so
+    // that every slice starts inside K ((nslices - 1) * cps < nchunks)
+    p.nslices = (dm.nchunks + p.cps - 1) / p.cps;
 }
 
 } // namespace
@@ -524,10 +533,19 @@ hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st)
     return hlq_hip_status(hipGetLastError());
 }
 
-hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws,
-                                 hipStream_t st)
+// The work split of a grouped launch: everything the host decides (formulation, workgroup shape, K
+// slices and runs per problem, block ranges, workspace carving).  Touches no device memory, so the
+// plan can also be inspected without a GPU (hlq_gemv_plan_query).
+struct GemvLaunchShape {
+    bool mx;
+    int W, TN, rows;
+    long nblocks;
+    size_t ws_used;   // bytes of the workspace this plan touches: the counter block and its partial sums
+};
+
+static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws, GemvBatch &b,
+                                  GemvLaunchShape &ls)
 {
-    hlq_clear_stale_error();
     if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
     long units = 0;
     for (int i = 0; i < count; ++i) units += (long)items[i].dm.ntiles * items[i].dm.nchunks;
@@ -542,8 +560,8 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         // launches, longer runs and eight wavefronts once there are enough tiles
         pl.W = units < 4096 ? 4 : 8;
         pl.cpw = units < 4096 ? 2 : units < 12000 ? 4 : 6;
-        if (g_plan_w) pl.W = g_plan_w;
-        if (g_plan_cpw) pl.cpw = g_plan_cpw;
+        if (const int v = g_plan_w.load(std::memory_order_relaxed)) pl.W = v;
+        if (const int v = g_plan_cpw.load(std::memory_order_relaxed)) pl.cpw = v;
     }
     {
         const int q0 = items[0].dm.q, G0 = items[0].dm.G;
@@ -558,7 +576,6 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     int cps = slice_chunks(pl);
     if (cps < 4) cps = 4;
 
-    GemvBatch b;
     b.count = count;
     b.out_f32 = out == HLQ_OUT_F32;
     int *cnt = (int *)ws;
@@ -595,7 +612,10 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
             p.ntg = (dm.ntiles + pl.TN - 1) / pl.TN;
             p.nslices = slices_for(dm, cps);
             p.cps = ((dm.nchunks + p.nslices - 1) / p.nslices + 1) & ~1;   // even split, even boundaries
+            p.nslices = slices_for(dm, p.cps);
         }
+        // every K slice must start inside K: the kernels form addresses from a slice's first chunk
+        if (p.nslices < 1 || p.cps < 1 || (long)(p.nslices - 1) * p.cps >= dm.nchunks) return HLQ_ERR_UNSUPPORTED;
         p.kw_shift = 0;
         while ((1 << p.kw_shift) < p.kw) ++p.kw_shift;
         // exact for local * nslices < 2^32, far above any grid this library launches (checked below)
@@ -616,24 +636,97 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
         b.blk_begin[i] = 0x7fffffff;
     }
     if (cnt_used > HLQ_WS_COUNTER_BYTES / 4 || blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
+    ls.mx = mx;
+    ls.W = pl.W;
+    ls.TN = pl.TN;
+    ls.rows = rows;
+    ls.nblocks = blk;
+    ls.ws_used = HLQ_WS_COUNTER_BYTES + (size_t)(part - (float *)((char *)ws + HLQ_WS_COUNTER_BYTES)) * sizeof(float);
+    return HLQ_OK;
+}
 
+hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws,
+                                 hipStream_t st, size_t ws_cap)
+{
+    hlq_clear_stale_error();
+    GemvBatch b;
+    GemvLaunchShape ls;
+    hlq_status s = plan_gemv_batch(count, items, out, ws, b, ls);
+    if (s != HLQ_OK) return s;
+    if (ws_cap && ls.ws_used > ws_cap) return HLQ_ERR_BUFFER_TOO_SMALL;   // checked on the plan that is launched
     const int q = items[0].dm.q, G = items[0].dm.G;
-    hlq_status s;
-    if (mx) {
-        const int nsets = rows == 1 ? 0 : rows <= hlq_gemv_mx_rows_per_set(G) ? 1 : 2;
-        s = hlq_launch_gemv_mx(b, (unsigned)blk, pl.W, nsets, rows, q, G, st);
+    const unsigned blk = (unsigned)ls.nblocks;
+    if (ls.mx) {
+        const int nsets = ls.rows == 1 ? 0 : ls.rows <= hlq_gemv_mx_rows_per_set(G) ? 1 : 2;
+        s = hlq_launch_gemv_mx(b, blk, ls.W, nsets, ls.rows, q, G, st);
         if (s != HLQ_OK) return s;
         return hlq_hip_status(hipGetLastError());
     }
     switch (q) {
-    case 1: s = launch_q<1>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
-    case 2: s = launch_q<2>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
-    case 3: s = launch_q<3>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
-    case 4: s = launch_q<4>(G, b, (unsigned)blk, pl.W, pl.TN, st); break;
+    case 1: s = launch_q<1>(G, b, blk, ls.W, ls.TN, st); break;
+    case 2: s = launch_q<2>(G, b, blk, ls.W, ls.TN, st); break;
+    case 3: s = launch_q<3>(G, b, blk, ls.W, ls.TN, st); break;
+    case 4: s = launch_q<4>(G, b, blk, ls.W, ls.TN, st); break;
     default: return HLQ_ERR_UNSUPPORTED;
     }
     if (s != HLQ_OK) return s;
     return hlq_hip_status(hipGetLastError());
+}
+
+// Workspace bytes the GEMV of one matrix touches with the plan it would get now (at most the bound
+// hlq_workspace_bytes reports, usually far less: most plans cut K inside a workgroup only).
+hlq_status hlq_gemv_ws_used(const HlqDims &dm, size_t *bytes)
+{
+    HlqGemvItem it;
+    it.dm = dm;
+    it.packed = nullptr;
+    it.x = nullptr;
+    it.y = nullptr;
+    GemvBatch b;
+    GemvLaunchShape ls;
+    const hlq_status s = plan_gemv_batch(1, &it, HLQ_OUT_F16, nullptr, b, ls);
+    if (s == HLQ_OK) *bytes = ls.ws_used;
+    return s;
+}
+
+// The plan of a launch of `count` problems with M rows each, as hlq_launch_gemv_batch would make it now
+// (current knobs).  Host arithmetic only.
+hlq_status hlq_gemv_plan_describe(int count, const HlqDims *dms, int M, hlq_gemv_plan_info *out)
+{
+    HlqGemvItem items[HLQ_MAX_BATCH];
+    if (count < 1 || count > HLQ_MAX_BATCH) return HLQ_ERR_UNSUPPORTED;
+    for (int i = 0; i < count; ++i) {
+        items[i].dm = dms[i];
+        items[i].packed = nullptr;
+        items[i].x = nullptr;
+        items[i].y = nullptr;
+        items[i].M = M;
+        items[i].ldx = dms[i].K;
+        items[i].ldy = dms[i].N;
+    }
+    GemvBatch b;
+    GemvLaunchShape ls;
+    const hlq_status s = plan_gemv_batch(count, items, HLQ_OUT_F16, nullptr, b, ls);
+    if (s != HLQ_OK) return s;
+    bool taken[HLQ_MAX_BATCH] = {};
+    for (int i = 0; i < count; ++i) {
+        // problems are planned in launch order (long K first); report them in the caller's order
+        int at = -1;
+        for (int k = 0; k < count && at < 0; ++k)
+            if (!taken[k] && b.p[k].nchunks == dms[i].nchunks && b.p[k].N == dms[i].N && b.p[k].col_bytes == dms[i].col_bytes) at = k;
+        if (at < 0) return HLQ_ERR_UNSUPPORTED;
+        taken[at] = true;
+        const GemvProb &p = b.p[at];
+        out[i].formulation = ls.mx ? 2 : 1;
+        out[i].waves_per_workgroup = ls.W;
+        out[i].waves_per_tile = ls.mx ? p.kw : ls.W;
+        out[i].chunks_per_slice = p.cps;
+        out[i].slices = p.nslices;
+        out[i].tile_groups = p.ntg;
+        out[i].first_block = p.blk_begin;
+        out[i].blocks = (int32_t)((long)p.ntg * p.nslices);
+    }
+    return HLQ_OK;
 }
 
 // Rows an MX launch can carry for group size G (two row sets).

@@ -1,4 +1,5 @@
-// hlq_lut_gemv, matrix-core formulation of the bit-serial product (Sec. 2, Eq. 5-6):
+// hlq_lut_gemv, matrix-core formulation of the bit-serial product (Sec. 2, paragraph
+// "Bit-Serial LUT-Based GEMM", and App. B; weights in the format of Eq. 3):
 //
 //   y[n] = sum_groups ( sum_j s_j[g,n] * <b_j[.,n], x>_g  +  z[g,n] * sum_g(x) )
 //
@@ -157,7 +158,9 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
     const bool tile_ok = tile < P.ntiles;               // a surplus wavefront gets an empty run
     const int tile_c = tile_ok ? tile : P.ntiles - 1;
     // this wavefront's run of chunks: the slice is cut into KW near-equal parts
-    const int sbeg = slice * P.cps;
+    // (the host plans every slice to start inside K; the clamp keeps every address formed below inside the
+    // tile and inside x whatever the plan says)
+    const int sbeg = min(slice * P.cps, P.nchunks - 1);
     const int send = min(sbeg + P.cps, P.nchunks);
     const int len = send - sbeg;
     const int cbeg = sbeg + ((len * part) >> KSH);
@@ -201,8 +204,11 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
             asm volatile("" : "+v"(woff));
             v = __builtin_nontemporal_load((const int4v *)(record_of(ch) + (size_t)(j * tw * 16) + woff));
         } else {
-            const uint32_t so = hlq_rec_in_tile(tw, ch, Q, G) + (uint32_t)(j * tw * 16);
-            v = __builtin_bit_cast(int4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)woff, (int)so, 2));   // aux 2: non-temporal
+            // The record's offset goes into the per-lane offset, which the range check certainly covers;
+            // only the position inside the record is a scalar offset.  A record that starts inside the
+            // run lies inside it entirely, so the check on its start decides for all of its loads.
+            const uint32_t vo = woff + hlq_rec_in_tile(tw, ch, Q, G);
+            v = __builtin_bit_cast(int4v, __builtin_amdgcn_raw_buffer_load_b128(wrsrc, (int)vo, j * tw * 16, 2));   // aux 2: non-temporal
         }
         R.w[j][0] = v.x; R.w[j][1] = v.y; R.w[j][2] = v.z; R.w[j][3] = v.w;
     };
@@ -218,8 +224,8 @@ hlq_gemv_mx_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag,
                     asm volatile("" : "+v"(moff));   // per load, or the compiler adds lane offset and base once, in vector registers
                     R.mt[sg][r] = *(const uint16_t *)(record_of(cm) + (size_t)tw * Q * 16 + (size_t)((sg * (Q + 1) + r) * tw * 2) + moff);
                 } else {
-                    const uint32_t mo = hlq_rec_in_tile(tw, cm, Q, G) + (uint32_t)(tw * Q * 16 + (sg * (Q + 1) + r) * tw * 2);
-                    R.mt[sg][r] = __builtin_amdgcn_raw_buffer_load_b16(wrsrc, (int)moff, (int)mo, 0);
+                    const uint32_t vo = moff + hlq_rec_in_tile(tw, cm, Q, G);
+                    R.mt[sg][r] = __builtin_amdgcn_raw_buffer_load_b16(wrsrc, (int)vo, tw * Q * 16 + (sg * (Q + 1) + r) * tw * 2, 0);
                 }
             }
         // activations: plain loads; the chunk index stays inside the run (rows past M re-read the last row and are ignored)

@@ -104,13 +104,17 @@ struct HlqGemvItem {
     long ldx = 0, ldy = 0;  // row strides of x and y in elements (M > 1)
 };
 #define HLQ_MAX_BATCH 8
+// ws_cap: size of the workspace behind `ws` if the launch is to be refused when its plan needs more
+// (HLQ_ERR_BUFFER_TOO_SMALL); 0 = the caller has checked the documented bound already
 hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dtype out, void *ws,
-                                 hipStream_t st);
+                                 hipStream_t st, size_t ws_cap = 0);
 hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M,
                            int64_t ldx, void *Y, int64_t ldy, hlq_out_dtype out, void *ws,
                            hipStream_t st);
 hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st);
 hlq_status hlq_gemv_plan_override(int tn, int w, int cpw);
+hlq_status hlq_gemv_ws_used(const HlqDims &dm, size_t *bytes);
+hlq_status hlq_gemv_plan_describe(int count, const HlqDims *dms, int M, hlq_gemv_plan_info *out);
 hlq_status hlq_gemv_path_override(int path);
 
 // Workspace = [HLQ_WS_COUNTER_BYTES of split-K arrival counters][fp32 partial sums].

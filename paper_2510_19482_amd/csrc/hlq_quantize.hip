@@ -1,10 +1,11 @@
-// hlq_quantize: Alg. 1 (Sec. 3.2, "Alternating Optimization for Hierarchical Linear Quantization") --
+// hlq_quantize: Alg. 1 (Sec. 4.1, "Alternating Optimization for Hierarchical Linear Quantization"; its two steps are
+// defined in Sec. 4.2 under "Bit-Pattern Selection" and "Linear Reconstruction") --
 // produces the codes, per-plane scales and zero points that hlq_pack consumes.
 //
 //   per group of G consecutive k of a column:  Delta = (max - min) / (2^q - 1),
 //   s = [Delta, 2 Delta, ...], z = min;  then T_max times
-//     bit-pattern selection   code = argmin_c | (w - z) - sum_j s_j bit_j(c) |      (Eq. 9)
-//     linear reconstruction   (s, z) = least squares of w ~ sum_j s_j b_j + z        (Eq. 10)
+//     bit-pattern selection   code = argmin_c | (w - z) - sum_j s_j bit_j(c) |      (Bit-Pattern Selection)
+//     linear reconstruction   (s, z) = least squares of w ~ sum_j s_j b_j + z        (Linear Reconstruction, LSE)
 //
 // Groups are independent (App. C), so the unit of work is one lane = one (group, column).  The lane
 // reads its G weights once, into registers (G fp32 values; lanes of a wavefront hold adjacent

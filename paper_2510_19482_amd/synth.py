@@ -110,7 +110,7 @@ def make_x(M: int, K: int, *key, outliers: bool = False) -> np.ndarray:
 
 def make_dense_weight(K: int, N: int, *key, std: float = 0.02) -> np.ndarray:
     """Unquantised weights W[K, N] fp32 ~ N(0, std): the bell shape the quantizer is designed for
-    (Sec. 3.1, Fig. 3)."""
+    (Sec. 3 "Motivation", Bell-Shaped Distribution of Weights; the weight-distribution figure there)."""
     rng = _rng("dense_weight", K, N, *key)
     return rng.normal(0.0, std, size=(K, N)).astype(np.float32)
 

@@ -100,7 +100,7 @@ def test_groups_with_few_distinct_values(q, G):
 
 
 def test_beats_round_to_nearest_at_size():
-    # a whole 8B-shaped projection matrix: properties that hold at any size (Fig. 3's claim; never
+    # a whole 8B-shaped projection matrix: properties that hold at any size (the claim of the MSE figure of Sec. 3; never
     # worse than the uniform grid it starts from), plus sampled groups against the oracle
     q, G, K, N = 2, 128, 4096, 1024
     W = synth.make_dense_weight(K, N, "big")

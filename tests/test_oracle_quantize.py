@@ -31,7 +31,7 @@ def test_first_selection_is_uniform_round_to_nearest(q, G):
 
 @pytest.mark.parametrize("q,G", [(2, 128), (3, 128), (4, 64), (1, 32)])
 def test_objective_never_increases(q, G):
-    # selection minimises over B with (s, z) fixed, LSE over (s, z) with B fixed (Eq. 9, Eq. 10)
+    # selection minimises over B with (s, z) fixed, LSE over (s, z) with B fixed (Sec. 4.2: Bit-Pattern Selection, Linear Reconstruction)
     W = gaussian(256, 16, "mono", q, G)
     _, _, _, hist = Q.quantize(W, q, G, t_max=6, history=True)
     assert hist.shape[0] == 12
@@ -48,7 +48,7 @@ def test_lse_equals_library_least_squares_on_full_rank_groups(q):
     s1, z1 = Q.lse(Wg, codes_g, s0, z0, q)
     for g in range(Wg.shape[0]):
         B = np.stack([(codes_g[g] >> j) & 1 for j in range(q)], axis=1).astype(np.float64)
-        A = np.concatenate([B, np.ones((G, 1))], axis=1)          # Eq. 10: [B 1] [s; z]
+        A = np.concatenate([B, np.ones((G, 1))], axis=1)          # Linear Reconstruction: [B 1] [s; z]
         if np.linalg.matrix_rank(A) < q + 1:
             continue
         sol = np.linalg.lstsq(A, Wg[g], rcond=None)[0]
@@ -99,7 +99,7 @@ def test_brute_force_lower_bound_and_fixed_point_on_tiny_groups(q, G):
 
 @pytest.mark.parametrize("q", [2, 3])
 def test_beats_round_to_nearest_on_gaussian_weights(q):
-    # Fig. 3 / Sec. 3.2: on bell-shaped weights the fitted grid has clearly lower error than the uniform one
+    # MSE figure of Sec. 3 / Sec. 4.2: on bell-shaped weights the fitted grid has clearly lower error than the uniform one
     G = 128
     W = gaussian(512, 32, "fig3", q)
     codes, S, Z = Q.quantize(W, q, G, t_max=10)
