@@ -93,7 +93,7 @@ HLQ_API hlq_status hlq_batch_workspace_bytes(int count, const hlq_desc *descs, s
  * start at zero that moment never comes, or comes early: the affected outputs are then not written
  * at all (they keep what y held) or are sums over the slices that happened to be there.  No fault, no
  * error code -- wrong numbers.  Launches whose plan does not split K across workgroups do not
- * touch the workspace. */
+ * touch the workspace.  hlq_lut_gemv_static needs no such call. */
 HLQ_API hlq_status hlq_workspace_init(void *ws, size_t ws_bytes, void *stream);
 
 /* Alg. 1 (Sec. 4.1; its steps "Bit-Pattern Selection" and "Linear Reconstruction" are defined in
@@ -139,6 +139,23 @@ HLQ_API hlq_status hlq_unpack(const hlq_desc *d, const void *packed, uint8_t *co
  *   ws / ws_bytes: workspace of at least hlq_workspace_bytes(d, 1). */
 HLQ_API hlq_status hlq_lut_gemv(const hlq_desc *d, const void *packed, const uint16_t *x, void *y,
                         hlq_out_dtype out, void *ws, size_t ws_bytes, void *stream);
+
+/* hlq_lut_gemv for callers that cannot allocate device memory and therefore have no workspace to
+ * pass: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * kernels and results as hlq_lut_gemv; the split-K counters and partial sums live in a fixed
+ * array of HLQ_STATIC_SCRATCH_BYTES inside the library, one copy per GPU, held until the
+ * process ends.  The call allocates nothing and needs no hlq_workspace_init.
+ *   - the device that owns `stream` must be the current device of the calling thread;
+ *   - a GEMV whose launch plan needs more partial sums than the array holds is refused with
+ *     HLQ_ERR_BUFFER_TOO_SMALL before anything is launched (every LLaMA-3.1-8B / 70B layer shape
+ *     and the 128256-wide head fit with the built-in plans; forced plans with many K slices on very
+ *     wide matrices may not);
+ *   - all calls on one GPU share that GPU's array: calls that may overlap in time on one GPU
+ *     (different streams, or graphs replayed concurrently) race on it and must use hlq_lut_gemv
+ *     with separate workspaces instead.  Calls in stream order are fine, also mixed shapes. */
+#define HLQ_STATIC_SCRATCH_BYTES ((size_t)131072 + ((size_t)4 << 20))
+HLQ_API hlq_status hlq_lut_gemv_static(const hlq_desc *d, const void *packed, const uint16_t *x, void *y,
+                                       hlq_out_dtype out, void *stream);
 
 /* `count` (1..8) independent GEMVs y_i = x_i @ W^_i in ONE launch (the decode GEMVs of a
  * layer that do not depend on each other, e.g. q/k/v or gate/up).  All descriptors must share

@@ -60,6 +60,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_unpack.argtypes = [dp, vp, vp, vp, vp, vp]
     lib.hlq_lut_gemv.restype = ctypes.c_int
     lib.hlq_lut_gemv.argtypes = [dp, vp, vp, vp, ctypes.c_int, vp, sz, vp]
+    lib.hlq_lut_gemv_static.restype = ctypes.c_int
+    lib.hlq_lut_gemv_static.argtypes = [dp, vp, vp, vp, ctypes.c_int, vp]
     lib.hlq_batch_workspace_bytes.restype = ctypes.c_int
     lib.hlq_batch_workspace_bytes.argtypes = [ctypes.c_int, dp, szp]
     lib.hlq_workspace_init.restype = ctypes.c_int
@@ -285,6 +287,17 @@ def hlq_lut_gemv(desc: HlqDesc, packed, x, y=None, out_f32: bool = False, ws=Non
     _check("hlq_lut_gemv", lib.hlq_lut_gemv(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(y),
                                             HLQ_OUT_F32 if out_f32 else HLQ_OUT_F16, _ptr(ws), ws.numel(),
                                             _stream_ptr(stream)))
+    return y
+
+
+STATIC_SCRATCH_BYTES = 131072 + (4 << 20)
+
+
+def hlq_lut_gemv_static(desc: HlqDesc, packed, x, y, out_f32: bool = False, stream=None):
+    """hlq_lut_gemv without a workspace argument (scratch in a fixed array of the library); `y` is
+    the caller's output tensor: this call allocates nothing."""
+    _check("hlq_lut_gemv_static", lib.hlq_lut_gemv_static(ctypes.byref(desc), _ptr(packed), _ptr(x), _ptr(y),
+                                                          HLQ_OUT_F32 if out_f32 else HLQ_OUT_F16, _stream_ptr(stream)))
     return y
 
 
