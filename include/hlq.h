@@ -225,7 +225,9 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
  *     GEMV kernel of hlq_set_gemv_path(2) with several activation rows per operand, above that
  *     the tiled kernel that rebuilds W^ in fp16 registers (hlq_lut_gemm_batch keeps up to twice
  *     as many rows on the GEMV kernel, where one launch for several problems pays),
- * 3 = as 2 but never the few-rows GEMV kernel.
+ * 3 = as 2 but never the few-rows GEMV kernel,
+ * 4 = as 2, and hlq_lut_gemm_batch keeps up to 16 rows (G >= 128) on the many-rows kernel, which by
+ *     default takes 5..8 rows only.
  * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel requires |s_j| < 512. */
 HLQ_API hlq_status hlq_set_gemm_path(int path);
 
@@ -248,6 +250,13 @@ HLQ_API hlq_status hlq_lut_gemm(const hlq_desc *d, const void *packed, const uin
  *   8192 for blocks = 0 (else HLQ_ERR_BUFFER_TOO_SMALL). */
 HLQ_API hlq_status hlq_stream_read(const void *src, size_t bytes, int blocks, void *sink, size_t sink_bytes,
                                    void *stream);
+
+/* The same read with its shape as arguments, for sweeps that look for the fastest plain read the
+ * machine does on a given footprint: `unroll` independent 128-bit loads in flight per lane and loop
+ * trip (1, 2, 4, 8 or 16; else HLQ_ERR_UNSUPPORTED), `temporal` != 0 for default-policy loads
+ * instead of streaming (non-temporal) ones.  hlq_stream_read is unroll 4, streaming. */
+HLQ_API hlq_status hlq_stream_read_shaped(const void *src, size_t bytes, int blocks, int unroll, int temporal,
+                                          void *sink, size_t sink_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -87,6 +87,8 @@ def _load() -> ctypes.CDLL:
     lib.hlq_set_gemv_path.argtypes = [ctypes.c_int]
     lib.hlq_stream_read.restype = ctypes.c_int
     lib.hlq_stream_read.argtypes = [vp, sz, ctypes.c_int, vp, sz, vp]
+    lib.hlq_stream_read_shaped.restype = ctypes.c_int
+    lib.hlq_stream_read_shaped.argtypes = [vp, sz, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, sz, vp]
     lib.hlq_lut_gemm.restype = ctypes.c_int
     lib.hlq_lut_gemm.argtypes = [dp, vp, vp, i64, i64, vp, i64, ctypes.c_int, vp, sz, vp]
     return lib
@@ -125,7 +127,7 @@ def gemv_plan_query(descs, M: int = 1):
     return list(out)
 
 
-GEMM_AUTO, GEMM_LUT, GEMM_MFMA, GEMM_MFMA_FP16 = 0, 1, 2, 3
+GEMM_AUTO, GEMM_LUT, GEMM_MFMA, GEMM_MFMA_FP16, GEMM_ROWS16 = 0, 1, 2, 3, 4
 
 
 def set_gemm_path(path: int = 0) -> None:
@@ -227,6 +229,14 @@ def hlq_stream_read(src, nbytes: int, sink, blocks: int = 0, offset: int = 0, st
     """Measurement helper: read nbytes of `src` (a cuda tensor) from byte `offset` on, once."""
     _check("hlq_stream_read", lib.hlq_stream_read(_ptr(src) + offset, nbytes, blocks, _ptr(sink),
                                                   sink.numel() * sink.element_size(), _stream_ptr(stream)))
+
+
+def hlq_stream_read_shaped(src, nbytes: int, sink, blocks: int = 0, unroll: int = 4, temporal: bool = False,
+                           offset: int = 0, stream=None):
+    """hlq_stream_read with its loop shape and cache policy as arguments (for sweeps)."""
+    _check("hlq_stream_read_shaped", lib.hlq_stream_read_shaped(_ptr(src) + offset, nbytes, blocks, unroll, int(temporal),
+                                                                _ptr(sink), sink.numel() * sink.element_size(),
+                                                                _stream_ptr(stream)))
 
 
 class GemvBatch:

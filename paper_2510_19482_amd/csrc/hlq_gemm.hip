@@ -255,7 +255,7 @@ static std::atomic<int> g_gemm_path{0};
 
 hlq_status hlq_gemm_path_override(int path)
 {
-    if (path < 0 || path > 3) return HLQ_ERR_UNSUPPORTED;
+    if (path < 0 || path > 4) return HLQ_ERR_UNSUPPORTED;
     g_gemm_path = path;
     return HLQ_OK;
 }
@@ -272,6 +272,9 @@ static bool use_mfma(int64_t M)
 
 // true if hlq_launch_gemm sends M rows (that fit one pass) to the few-rows matrix-core GEMV kernel
 bool hlq_gemm_uses_mx_rows(int64_t M) { return use_mfma(M) && g_gemm_path.load(std::memory_order_relaxed) != 3; }
+
+// true if the many-rows kernel is to take all the rows it can carry (hlq_set_gemm_path(4))
+bool hlq_gemm_rows_all() { return g_gemm_path.load(std::memory_order_relaxed) == 4; }
 
 // true if hlq_launch_gemm computes M rows on the matrix cores (either kernel)
 bool hlq_gemm_uses_matrix_cores(int64_t M) { return use_mfma(M); }

@@ -538,6 +538,7 @@ hlq_status hlq_launch_ws_init(void *ws, size_t bytes, hipStream_t st)
 // plan can also be inspected without a GPU (hlq_gemv_plan_query).
 struct GemvLaunchShape {
     bool mx;
+    bool rowsk;       // the many-rows kernel (hlq_gemm_rows.hip) instead of the few-rows instantiation of the GEMV kernel
     int W, TN, rows;
     long nblocks;
     size_t ws_used;   // bytes of the workspace this plan touches: the counter block and its partial sums
@@ -554,8 +555,18 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
     for (int i = 1; i < count; ++i)
         if (items[i].M != rows) return HLQ_ERR_UNSUPPORTED;
     if (rows < 1 || rows > hlq_gemm_mx_rows_per_pass(items[0].dm.G)) return HLQ_ERR_UNSUPPORTED;
-    const bool mx = use_mx() || rows > 1;   // several activation rows exist in the matrix-core kernel only
-    if (rows > 1) {
+    const bool mx = use_mx() || rows > 1;   // several activation rows exist in the matrix-core kernels only
+    // more rows than one operand of the GEMV kernel holds: the many-rows kernel (terms chained through the
+    // accumulator, activations converted once per workgroup), where it exists for this group size
+    const bool rowsk = rows > hlq_gemv_mx_rows_per_set(items[0].dm.G) && rows <= hlq_gemm_rows_max(items[0].dm.G) &&
+                       rows <= hlq_gemm_mx_rows_per_pass(items[0].dm.G);
+    if (rowsk) {
+        pl.W = 4;
+        // chunks per K slice: long enough that the partial sums (rows x columns x slices) stay a small part of the
+        // traffic, short enough that the launch has several workgroups per compute unit
+        pl.cpw = units < 12000 ? 4 : 8;
+        if (const int v = g_plan_cpw.load(std::memory_order_relaxed)) pl.cpw = v < 4 ? 4 : v;
+    } else if (rows > 1) {
         // measured (8B shapes, q = 4, M = 2..8): short runs on few wavefronts per workgroup for narrow
         // launches, longer runs and eight wavefronts once there are enough tiles
         pl.W = units < 4096 ? 4 : 8;
@@ -568,6 +579,10 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
         if (mx || !gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
         const int maxw = mx ? hlq_gemv_mx_max_waves(q0, G0) : gemv_max_threads(q0, G0, pl.TN) / 64;
         if (pl.W > maxw) pl.W = maxw;
+        if (rowsk) {
+            pl.W = 4;
+            if (const int v = g_plan_w.load(std::memory_order_relaxed)) pl.W = v >= 8 ? 8 : v >= 4 ? 4 : 2;
+        }
         if (mx)   // a power of two
             while (pl.W & (pl.W - 1)) pl.W &= pl.W - 1;
     }
@@ -606,7 +621,9 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
         p.M = rows;
         p.ldx = items[order[i]].ldx;
         p.ldy = items[order[i]].ldy;
-        if (mx) {
+        if (rowsk) {
+            plan_mx_problem(dm, pl.W, pl.cpw, p);
+        } else if (mx) {
             plan_mx_problem(dm, pl.W, pl.cpw, p);
         } else {
             p.ntg = (dm.ntiles + pl.TN - 1) / pl.TN;
@@ -637,6 +654,7 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
     }
     if (cnt_used > HLQ_WS_COUNTER_BYTES / 4 || blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
     ls.mx = mx;
+    ls.rowsk = rowsk;
     ls.W = pl.W;
     ls.TN = pl.TN;
     ls.rows = rows;
@@ -656,6 +674,11 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     if (ws_cap && ls.ws_used > ws_cap) return HLQ_ERR_BUFFER_TOO_SMALL;   // checked on the plan that is launched
     const int q = items[0].dm.q, G = items[0].dm.G;
     const unsigned blk = (unsigned)ls.nblocks;
+    if (ls.rowsk) {
+        s = hlq_launch_gemm_rows(b, blk, ls.W, ls.rows, q, G, st);
+        if (s != HLQ_OK) return s;
+        return hlq_hip_status(hipGetLastError());
+    }
     if (ls.mx) {
         const int nsets = ls.rows == 1 ? 0 : ls.rows <= hlq_gemv_mx_rows_per_set(G) ? 1 : 2;
         s = hlq_launch_gemv_mx(b, blk, ls.W, nsets, ls.rows, q, G, st);
@@ -730,7 +753,15 @@ hlq_status hlq_gemv_plan_describe(int count, const HlqDims *dms, int M, hlq_gemv
 }
 
 // Rows an MX launch can carry for group size G (two row sets).
-int hlq_gemm_mx_rows_per_pass(int G) { return 2 * hlq_gemv_mx_rows_per_set(G); }
+int hlq_gemm_mx_rows_per_pass(int G)
+{
+    // the many-rows kernel carries 16 rows, but from 9 rows on (four chained operands per item) one launch of the
+    // tiled kernel is faster on the measured shapes: by default it takes up to 8 rows, with hlq_set_gemm_path(4) all 16
+    const int two_sets = 2 * hlq_gemv_mx_rows_per_set(G);
+    int many = hlq_gemm_rows_max(G);
+    if (many > 8 && !hlq_gemm_rows_all()) many = 8;
+    return many > two_sets ? many : two_sets;
+}
 
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M)
 {

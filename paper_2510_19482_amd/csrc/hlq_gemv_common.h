@@ -81,3 +81,7 @@ __device__ __forceinline__ void store_out(void *y, size_t idx, float v, int out_
 // per tile: ntg = ceil(ntiles / (W / kw)) tile groups, one arrival counter per TILE
 hlq_status hlq_launch_gemv_mx(const GemvBatch &b, unsigned nblocks, int W, int nsets, int rows, int q, int G, hipStream_t st);
 int hlq_gemv_mx_max_waves(int q, int G);
+
+// many-rows kernel (hlq_gemm_rows.hip): W = 2, 4 or 8 wavefronts, one tile each, all on the workgroup's K slice
+hlq_status hlq_launch_gemm_rows(const GemvBatch &b, unsigned nblocks, int W, int rows, int q, int G, hipStream_t st);
+int hlq_gemm_rows_max(int G);

@@ -136,6 +136,7 @@ size_t hlq_gemm_mfma_batch_partial_bytes(int count, const HlqDims *dms, int64_t 
 int hlq_gemv_mx_rows_per_set(int G);
 int hlq_gemm_mx_rows_per_pass(int G);
 bool hlq_gemm_uses_mx_rows(int64_t M);
+bool hlq_gemm_rows_all();
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M);
 hlq_status hlq_launch_gemm_mx_rows(const HlqDims &dm, const void *packed, const uint16_t *X, int64_t M, int64_t ldx,
                                    void *Y, int64_t ldy, hlq_out_dtype out, void *ws, hipStream_t st);

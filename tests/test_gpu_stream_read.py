@@ -26,3 +26,25 @@ def test_checksum_covers_every_word_once(nbytes, blocks, offset):
     got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32)[:launched])
     want = np.bitwise_xor.reduce(host[offset // 4: (offset + nbytes) // 4])
     assert got == want
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8, 16])
+@pytest.mark.parametrize("temporal", [False, True])
+def test_shaped_read_covers_every_word_once(unroll, temporal):
+    nbytes, blocks, offset = (3 << 20) + 16 * 37, 96, 48
+    print("stream_read_shaped", unroll, temporal, flush=True)
+    rng = np.random.default_rng(unroll + 17 * temporal)
+    host = rng.integers(0, 2**32, size=(offset + nbytes) // 4 + 8, dtype=np.uint32)
+    buf = torch.from_numpy(host.view(np.int32)).cuda()
+    sink = torch.zeros(blocks, dtype=torch.int32, device="cuda")
+    B.hlq_stream_read_shaped(buf, nbytes, sink, blocks=blocks, unroll=unroll, temporal=temporal, offset=offset)
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    assert got == np.bitwise_xor.reduce(host[offset // 4: (offset + nbytes) // 4])
+
+
+def test_shaped_read_rejects_other_unrolls():
+    buf = torch.zeros(1024, dtype=torch.int32, device="cuda")
+    with pytest.raises(B.HlqError) as e:
+        B.hlq_stream_read_shaped(buf, 4096, buf, unroll=3)
+    assert e.value.status == 3
