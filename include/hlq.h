@@ -228,7 +228,9 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
  * 3 = as 2 but never the few-rows GEMV kernel,
  * 4 = as 2, and hlq_lut_gemm_batch keeps up to 16 rows (G >= 128) on the many-rows kernel, which by
  *     default takes 5..8 rows only.
- * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel requires |s_j| < 512. */
+ * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel represents scales up to |s_j| < 512 (and
+ * zeros of that size); it checks what it loads, and a call whose weights lie outside is computed again
+ * by an fp32 kernel launched behind it (slow, but right for every finite fp16 parameter). */
 HLQ_API hlq_status hlq_set_gemm_path(int path);
 
 /* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded

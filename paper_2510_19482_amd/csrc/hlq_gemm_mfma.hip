@@ -24,8 +24,10 @@
 // (2 * b, 2 * b).  One v_pk_fma_f16 per plane with the pre-scaled scale (s * 2^7 or s / 2) adds
 // s_j * b_j for two weights; the chain starts from (z, z).  Cost: 8 shifts + 16 ANDs per word and
 // plane, 16*q packed FMAs per word: about 2.3 VALU lane-ops per weight at q = 2.
-// Precondition of this path: |s_j| < 512 (pre-scaling by 2^7 must stay finite in fp16) -- HLQ
-// scales are weight magnitudes, orders of magnitude below that.
+// Range of this path: |s_j| < 512 (pre-scaling by 2^7 must stay finite in fp16) -- HLQ scales are
+// weight magnitudes, orders of magnitude below that.  The kernel checks every scale and zero it
+// loads; if one is outside, it raises a flag and the fp32 fallback launched behind it
+// (hlq_gemm_safe.hip) computes the call again, so any finite fp16 parameters give a right result.
 //
 // Contraction order.  Register pair p of a word holds k0 = 2p, 2p+1, so registers 8ks .. 8ks+7
 // hold the 16 consecutive k of k-step ks in natural order and every A fragment is one aligned
@@ -71,7 +73,7 @@ template <int Q, int G, int MW>
 __device__ __forceinline__ void gemm_mfma_block(const char *__restrict__ packed, size_t col_bytes,
                                                 const uint16_t *__restrict__ X, long ldx, int M, void *__restrict__ Y,
                                                 long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks, int cps,
-                                                int nslices, int out_f32, int bx, int by, int bz)
+                                                int nslices, int out_f32, int bx, int by, int bz, int *range_flag)
 {
     using Regs = WRegs<Q, G>;
     constexpr int GS = Regs::GS, SEG = Regs::SEG;
@@ -154,7 +156,14 @@ __device__ __forceinline__ void gemm_mfma_block(const char *__restrict__ packed,
     //   - the 16 weight pairs of word d + 1 are rebuilt 16 / (2 MW) per step during word d;
     //   - the four lane exchanges that form the B operands of the next k-step are spread over the MW
     //     steps of the current one.
+    // largest magnitude (as an fp16 bit pattern) among the scales and zeros this lane has used: the rebuild below is
+    // only valid while s * 2^7 and the partial sums of z + sum s_j b_j stay finite in fp16
+    uint32_t meta_max = 0;
     auto compute = [&](const Regs &R, int buf) {
+#pragma unroll
+        for (int sg = 0; sg < SEG; ++sg)
+#pragma unroll
+            for (int r = 0; r <= Q; ++r) meta_max = max(meta_max, R.mt[sg][r] & 0x7fffu);
         const size_t xb = (size_t)buf * ROWS * XROW;
         constexpr int STEPS = 8 * MW, SPW = 2 * MW, PPS = 16 / SPW, XPS = (4 + MW - 1) / MW;
         auto frag = [&](int s) -> half8v {
@@ -243,6 +252,10 @@ __device__ __forceinline__ void gemm_mfma_block(const char *__restrict__ packed,
         }
     }
 
+    // a scale of magnitude >= 512 (or a zero that large, or a non-finite value): raise the flag that makes the fallback
+    // kernel behind this launch compute the call again in fp32
+    if (__builtin_amdgcn_ballot_w64(meta_max >= 0x6000u) != 0 && lane == 0)
+        __hip_atomic_store(range_flag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     // ---- store: D tile register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32 ----------------
     if (tile >= ntiles) return;
     const int rbase = m0 + 4 * (lane >> 5);
@@ -276,10 +289,10 @@ template <int Q, int G, int MW>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 hlq_gemm_mfma_kernel(const char *__restrict__ packed, size_t col_bytes, const uint16_t *__restrict__ X, long ldx,
                      int M, void *__restrict__ Y, long ldy, float *__restrict__ ws, int N, int ntiles, int nchunks,
-                     int cps, int nslices, int out_f32)
+                     int cps, int nslices, int out_f32, int *range_flag)
 {
     gemm_mfma_block<Q, G, MW>(packed, col_bytes, X, ldx, M, Y, ldy, ws, N, ntiles, nchunks, cps, nslices, out_f32,
-                              (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z);
+                              (int)blockIdx.x, (int)blockIdx.y, (int)blockIdx.z, range_flag);
 }
 
 // Several problems with the same q, G and M in one launch (hlq_lut_gemm_batch): workgroups are numbered
@@ -313,7 +326,8 @@ __device__ __forceinline__ int group_problem_of(const int4v &bb_lo, const int4v 
 
 template <int Q, int G, int MW>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
-hlq_gemm_mfma_group_kernel(const int4v bb_lo, const int4v bb_hi, const int M, const int out_f32, const GemmProbs probs)
+hlq_gemm_mfma_group_kernel(const int4v bb_lo, const int4v bb_hi, const int M, const int out_f32, int *range_flag,
+                           const GemmProbs probs)
 {
     const int blk = (int)blockIdx.x;
     const GemmProb P = probs.p[group_problem_of(bb_lo, bb_hi, blk)];
@@ -323,7 +337,7 @@ hlq_gemm_mfma_group_kernel(const int4v bb_lo, const int4v bb_hi, const int M, co
     const int rb = P.nslices > 1 ? (int)__umulhi((unsigned)t, P.ns_magic) : t;
     const int sl = t - rb * P.nslices;
     gemm_mfma_block<Q, G, MW>(P.packed, P.col_bytes, P.X, P.ldx, M, P.Y, P.ldy, P.part, P.N, P.ntiles, P.nchunks,
-                              P.cps, P.nslices, out_f32, cg, sl, rb);
+                              P.cps, P.nslices, out_f32, cg, sl, rb, range_flag);
 }
 
 // adds the partial sums of all problems of a grouped launch whose K was split; 256 outputs per block
@@ -410,8 +424,10 @@ void launch_one(const HlqDims &dm, const MfmaPlan &p, const char *packed, const 
 {
     const dim3 grid((unsigned)((dm.ntiles + 3) / 4), (unsigned)p.nslices, (unsigned)p.rowblocks);
     const size_t lds = (size_t)2 * 32 * MW * XROW * sizeof(_Float16);
+    // ws points at the partial sums, which follow the counter block
+    int *range_flag = hlq_ws_range_flag((char *)ws - HLQ_WS_COUNTER_BYTES);
     hlq_gemm_mfma_kernel<Q, G, MW><<<grid, 256, lds, st>>>(packed, dm.col_bytes, X, ldx, M, Y, ldy, ws, dm.N, dm.ntiles,
-                                                          dm.nchunks, p.cps, p.nslices, out_f32);
+                                                          dm.nchunks, p.cps, p.nslices, out_f32, range_flag);
 }
 
 template <int Q, int G>
@@ -439,26 +455,26 @@ hlq_status launch_q(const HlqDims &dm, const MfmaPlan &p, const char *packed, co
 }
 
 template <int Q, int G>
-void launch_group_qg(int MW, unsigned nblocks, const int4v &lo, const int4v &hi, int M, int out_f32, const GemmProbs &pr,
-                     hipStream_t st)
+void launch_group_qg(int MW, unsigned nblocks, const int4v &lo, const int4v &hi, int M, int out_f32, int *flag,
+                     const GemmProbs &pr, hipStream_t st)
 {
     const size_t lds = (size_t)2 * 32 * MW * XROW * sizeof(_Float16);
     switch (MW) {
-    case 1: hlq_gemm_mfma_group_kernel<Q, G, 1><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, pr); break;
-    case 2: hlq_gemm_mfma_group_kernel<Q, G, 2><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, pr); break;
-    default: hlq_gemm_mfma_group_kernel<Q, G, 4><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, pr); break;
+    case 1: hlq_gemm_mfma_group_kernel<Q, G, 1><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, flag, pr); break;
+    case 2: hlq_gemm_mfma_group_kernel<Q, G, 2><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, flag, pr); break;
+    default: hlq_gemm_mfma_group_kernel<Q, G, 4><<<nblocks, 256, lds, st>>>(lo, hi, M, out_f32, flag, pr); break;
     }
 }
 
 template <int Q>
 hlq_status launch_group_q(int G, int MW, unsigned nblocks, const int4v &lo, const int4v &hi, int M, int out_f32,
-                          const GemmProbs &pr, hipStream_t st)
+                          int *flag, const GemmProbs &pr, hipStream_t st)
 {
     switch (G) {
-    case 32: launch_group_qg<Q, 32>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
-    case 64: launch_group_qg<Q, 64>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
-    case 128: launch_group_qg<Q, 128>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
-    case 256: launch_group_qg<Q, 256>(MW, nblocks, lo, hi, M, out_f32, pr, st); return HLQ_OK;
+    case 32: launch_group_qg<Q, 32>(MW, nblocks, lo, hi, M, out_f32, flag, pr, st); return HLQ_OK;
+    case 64: launch_group_qg<Q, 64>(MW, nblocks, lo, hi, M, out_f32, flag, pr, st); return HLQ_OK;
+    case 128: launch_group_qg<Q, 128>(MW, nblocks, lo, hi, M, out_f32, flag, pr, st); return HLQ_OK;
+    case 256: launch_group_qg<Q, 256>(MW, nblocks, lo, hi, M, out_f32, flag, pr, st); return HLQ_OK;
     }
     return HLQ_ERR_UNSUPPORTED;
 }
@@ -493,6 +509,16 @@ hlq_status hlq_launch_gemm_mfma(const HlqDims &dm, const void *packed, const uin
         hlq_gemm_mfma_reduce_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(part, Y, (long)ldy, (int)M, dm.N,
                                                                                     p.nslices, out_f32);
     }
+    // behind it, the fp32 fallback for weights outside the range of the fp16 rebuild (a no-op unless the flag went up)
+    HlqGemvItem it;
+    it.dm = dm;
+    it.packed = packed;
+    it.x = X;
+    it.y = Y;
+    it.ldx = (long)ldx;
+    it.ldy = (long)ldy;
+    s = hlq_launch_gemm_safe(1, &it, M, out, ws, st);
+    if (s != HLQ_OK) return s;
     return hlq_hip_status(hipGetLastError());
 }
 
@@ -610,10 +636,10 @@ hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64
     const int out_f32 = out == HLQ_OUT_F32;
     hlq_status s;
     switch (items[0].dm.q) {
-    case 1: s = launch_group_q<1>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
-    case 2: s = launch_group_q<2>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
-    case 3: s = launch_group_q<3>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
-    case 4: s = launch_group_q<4>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, pr, st); break;
+    case 1: s = launch_group_q<1>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, hlq_ws_range_flag(ws), pr, st); break;
+    case 2: s = launch_group_q<2>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, hlq_ws_range_flag(ws), pr, st); break;
+    case 3: s = launch_group_q<3>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, hlq_ws_range_flag(ws), pr, st); break;
+    case 4: s = launch_group_q<4>(items[0].dm.G, g.MW, (unsigned)blk, lo, hi, (int)M, out_f32, hlq_ws_range_flag(ws), pr, st); break;
     default: return HLQ_ERR_UNSUPPORTED;
     }
     if (s != HLQ_OK) return s;
@@ -625,5 +651,7 @@ hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64
         const int4v rlo = {rbegin[0], rbegin[1], rbegin[2], rbegin[3]}, rhi = {rbegin[4], rbegin[5], rbegin[6], rbegin[7]};
         hlq_gemm_mfma_group_reduce_kernel<<<(unsigned)rblk, 256, 0, st>>>(rlo, rhi, (int)M, out_f32, rp);
     }
+    s = hlq_launch_gemm_safe(count, items, M, out, ws, st);
+    if (s != HLQ_OK) return s;
     return hlq_hip_status(hipGetLastError());
 }

@@ -652,7 +652,7 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
         b.p[i] = b.p[0];
         b.blk_begin[i] = 0x7fffffff;
     }
-    if (cnt_used > HLQ_WS_COUNTER_BYTES / 4 || blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
+    if (cnt_used > HLQ_WS_ARRIVAL_COUNTERS || blk > 0x7fffffffL) return HLQ_ERR_UNSUPPORTED;
     ls.mx = mx;
     ls.rowsk = rowsk;
     ls.W = pl.W;

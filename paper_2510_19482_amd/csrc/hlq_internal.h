@@ -120,6 +120,28 @@ hlq_status hlq_gemv_path_override(int path);
 // Workspace = [HLQ_WS_COUNTER_BYTES of split-K arrival counters][fp32 partial sums].
 // Counters are zero between calls (hlq_workspace_init zeroes them; kernels re-zero them).
 #define HLQ_WS_COUNTER_BYTES 131072
+// The last two counters are not arrival counters: [0] is raised by the tiled matrix-core GEMM when it meets a
+// scale or zero outside the range its fp16 weight rebuild can represent, [1] counts the fallback kernel's
+// workgroups out (hlq_gemm_safe.hip).  Both are zero between calls, like the arrival counters.
+#define HLQ_WS_ARRIVAL_COUNTERS (HLQ_WS_COUNTER_BYTES / 4 - 2)
+static inline int *hlq_ws_range_flag(void *ws) { return (int *)ws + HLQ_WS_ARRIVAL_COUNTERS; }
+
+// one problem of the fallback launch
+struct HlqSafeProb {
+    const char *packed;
+    size_t col_bytes;
+    const uint16_t *X;
+    long ldx;
+    void *Y;
+    long ldy;
+    int N, ntiles, nchunks, q, G;
+    long item_begin;
+};
+struct HlqSafeProbs {
+    HlqSafeProb p[8];
+    int count;
+    long items_total;
+};
 size_t hlq_gemv_partial_bytes(const HlqDims &dm);
 size_t hlq_gemm_partial_bytes(const HlqDims &dm, int64_t M);
 size_t hlq_gemm_lut_partial_bytes(const HlqDims &dm, int64_t M);
@@ -133,6 +155,7 @@ bool hlq_gemm_uses_matrix_cores(int64_t M);
 hlq_status hlq_launch_gemm_mfma_batch(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, void *ws,
                                       hipStream_t st);
 size_t hlq_gemm_mfma_batch_partial_bytes(int count, const HlqDims *dms, int64_t M);
+hlq_status hlq_launch_gemm_safe(int count, const HlqGemvItem *items, int64_t M, hlq_out_dtype out, void *ws, hipStream_t st);
 int hlq_gemv_mx_rows_per_set(int G);
 int hlq_gemm_mx_rows_per_pass(int G);
 bool hlq_gemm_uses_mx_rows(int64_t M);

@@ -101,3 +101,64 @@ def test_mfma_equals_lut_path_within_tolerance():
     B.set_gemm_path(B.GEMM_LUT)
     b = gemm_gpu(d, packed, X, out_f32=True)
     assert O.row_rel_err(a, b).max() <= 1e-3
+
+
+# ---------------------------------------------------------------------------------------------------
+# Scales outside what the fp16 weight rebuild of the tiled kernel can represent (|s| >= 512: s * 2^7 is
+# not finite in fp16).  Any finite fp16 scale is a valid HLQ parameter (Eq. 3); the tiled kernel notices
+# such values and the fp32 kernel launched behind it computes the call again.
+@pytest.mark.parametrize("M", [40, 200])
+@pytest.mark.parametrize("big", [600.0, 30000.0])
+def test_large_scales_take_the_fp32_fallback(M, big):
+    from paper_2510_19482_amd import binding as B
+    from gpu_util import dev
+    K, N, q, G = 1024, 328, 2, 128
+    codes, S, Z = synth.make_weight(K, N, q, G, "bigscale")
+    S = S.copy()
+    S[0, 3, 17] = np.float16(big)           # one scale of one group of one column
+    S[1, 5, 200] = np.float16(-big)
+    X = synth.make_x(M, K, "bigscale", M)
+    d, packed = pack_on_gpu(codes, S, Z, q, G)
+    ref = O.gemm_dequant(X, codes, S, Z, q, G)
+    ws = B.alloc_workspace(d, M)
+    Y = B.hlq_lut_gemm(d, packed, dev(X), out_f32=True, ws=ws)
+    torch.cuda.synchronize()
+    Y = Y.cpu().numpy().astype(np.float64)
+    assert np.isfinite(Y).all()
+    assert O.row_rel_err(Y, ref).max() <= 2e-5          # fp32 throughout
+    # the flag is down again: the same workspace serves an ordinary call on the matrix cores next
+    assert int(ws[:131072].view(torch.int32).abs().sum().item()) == 0
+    codes2, S2, Z2 = synth.make_weight(K, N, q, G, "bigscale-after")
+    d2, packed2 = pack_on_gpu(codes2, S2, Z2, q, G)
+    Y2 = B.hlq_lut_gemm(d2, packed2, dev(X), out_f32=True, ws=ws)
+    torch.cuda.synchronize()
+    assert O.row_rel_err(Y2.cpu().numpy().astype(np.float64), O.gemm_dequant(X, codes2, S2, Z2, q, G)).max() <= 1e-3
+    assert int(ws[:131072].view(torch.int32).abs().sum().item()) == 0
+
+
+def test_large_scales_in_a_grouped_launch():
+    # one problem of three has an out-of-range scale: the whole grouped call is recomputed, every problem right
+    from paper_2510_19482_amd import binding as B
+    from gpu_util import dev
+    M, q, G = 70, 3, 64
+    shapes = [synth.Shape("a", 512, 200), synth.Shape("b", 1024, 72), synth.Shape("c", 256, 520)]
+    descs, packs, Xs, Ys, refs = [], [], [], [], []
+    for i, s in enumerate(shapes):
+        codes, S, Z = synth.make_weight(s.K, s.N, q, G, "bigscale-group", s.name)
+        if i == 1:
+            S = S.copy()
+            S[2, 0, 5] = np.float16(65504.0)
+            Z = Z.copy()
+            Z[1, 9] = np.float16(-20000.0)
+        X = synth.make_x(M, s.K, "bigscale-group", s.name)
+        d, p = pack_on_gpu(codes, S, Z, q, G)
+        descs.append(d); packs.append(p); Xs.append(dev(X))
+        Ys.append(torch.full((M, s.N), 7.0, dtype=torch.float32, device="cuda"))
+        refs.append(O.gemm_dequant(X, codes, S, Z, q, G))
+    batch = B.GemmBatch(descs, packs, Xs, Ys, out_f32=True)
+    for rep in range(2):
+        batch.launch()
+        torch.cuda.synchronize()
+        for s, Y, ref in zip(shapes, Ys, refs):
+            assert O.row_rel_err(Y.cpu().numpy().astype(np.float64), ref).max() <= 2e-5, s.name
+        assert int(batch.ws[:131072].view(torch.int32).abs().sum().item()) == 0
