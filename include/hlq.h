@@ -215,6 +215,12 @@ HLQ_API hlq_status hlq_gemv_plan_query(int count, const hlq_desc *descs, int64_t
  * cores (plane words expanded to 4-bit floats, activations as an exact sum of four 8-bit
  * floats; the matrix core keeps 13 bits below the largest product of an 8-element run, so a
  * result can differ from exact fp32 accumulation by about 1e-4 of the products' magnitude).
+ * 3..6 = table lookups with the table stored as App. D discusses ("Mirror Storage", "Table
+ * Quantization"), in a plain kernel written for the comparison: 3 = sixteen fp32 entries (the
+ * reference of the comparison), 4 = mirror form, eight fp32 entries of the +-1 re-parametrisation,
+ * the other eight by negation (lossless), 5 = sixteen fp16 entries (lossy: entries rounded to
+ * nearest even), 6 = sixteen int8 entries with one fp32 scale per table (lossy; outside the 2e-3 bar
+ * on layer-sized problems with outlier activations).
  * Other values: HLQ_ERR_UNSUPPORTED.  Activations must be finite. */
 HLQ_API hlq_status hlq_set_gemv_path(int path);
 

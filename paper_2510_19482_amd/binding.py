@@ -135,6 +135,7 @@ def set_gemm_path(path: int = 0) -> None:
 
 
 GEMV_AUTO, GEMV_LUT, GEMV_MX = 0, 1, 2
+GEMV_TABLE_F32, GEMV_TABLE_MIRROR, GEMV_TABLE_F16, GEMV_TABLE_I8 = 3, 4, 5, 6
 
 
 def set_gemv_path(path: int = 0) -> None:

@@ -446,7 +446,14 @@ bool use_mx()
     static const int env_path = env_int("HLQ_GEMV_PATH", 0);
     const int knob = g_gemv_path.load(std::memory_order_relaxed);
     const int path = knob ? knob : env_path;
-    return path != 1;   // automatic: the matrix-core kernel is the faster one on every measured shape
+    return path == 0 || path == 2;   // automatic: the matrix-core kernel is the faster one on every measured shape
+}
+
+// table-storage variant of the lookup formulation (hlq_gemv_variants.hip): -1 = none (the hand-scheduled kernel)
+int table_variant()
+{
+    const int knob = g_gemv_path.load(std::memory_order_relaxed);
+    return knob >= 3 ? knob - 3 : -1;
 }
 
 GemvPlan plan_gemv(long units)
@@ -503,7 +510,7 @@ void plan_mx_problem(const HlqDims &dm, int W, int cpw, GemvProb &p)
 
 hlq_status hlq_gemv_path_override(int path)
 {
-    if (path < 0 || path > 2) return HLQ_ERR_UNSUPPORTED;
+    if (path < 0 || path > 6) return HLQ_ERR_UNSUPPORTED;
     g_gemv_path = path;
     return HLQ_OK;
 }
@@ -576,7 +583,7 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
     }
     {
         const int q0 = items[0].dm.q, G0 = items[0].dm.G;
-        if (mx || !gemv_two_tiles_ok(q0, G0)) pl.TN = 1;
+        if (mx || !gemv_two_tiles_ok(q0, G0) || table_variant() >= 0) pl.TN = 1;
         const int maxw = mx ? hlq_gemv_mx_max_waves(q0, G0) : gemv_max_threads(q0, G0, pl.TN) / 64;
         if (pl.W > maxw) pl.W = maxw;
         if (rowsk) {
@@ -682,6 +689,11 @@ hlq_status hlq_launch_gemv_batch(int count, const HlqGemvItem *items, hlq_out_dt
     if (ls.mx) {
         const int nsets = ls.rows == 1 ? 0 : ls.rows <= hlq_gemv_mx_rows_per_set(G) ? 1 : 2;
         s = hlq_launch_gemv_mx(b, blk, ls.W, nsets, ls.rows, q, G, st);
+        if (s != HLQ_OK) return s;
+        return hlq_hip_status(hipGetLastError());
+    }
+    if (table_variant() >= 0 && ls.TN == 1) {
+        s = hlq_launch_gemv_variant(table_variant(), b, blk, ls.W, q, G, st);
         if (s != HLQ_OK) return s;
         return hlq_hip_status(hipGetLastError());
     }

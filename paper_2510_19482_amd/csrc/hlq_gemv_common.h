@@ -85,3 +85,6 @@ int hlq_gemv_mx_max_waves(int q, int G);
 // many-rows kernel (hlq_gemm_rows.hip): W = 2, 4 or 8 wavefronts, one tile each, all on the workgroup's K slice
 hlq_status hlq_launch_gemm_rows(const GemvBatch &b, unsigned nblocks, int W, int rows, int q, int G, hipStream_t st);
 int hlq_gemm_rows_max(int G);
+
+// table-storage variants of the lookup formulation (hlq_gemv_variants.hip); batch planned as for hlq_gemv_kernel, TN = 1
+hlq_status hlq_launch_gemv_variant(int variant, const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st);

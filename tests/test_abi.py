@@ -129,11 +129,11 @@ def test_workspace_sizes_cover_every_path():
 
 
 def test_path_knobs_accept_documented_values_only():
-    for v in (0, 1, 2):
+    for v in (0, 1, 2, 3, 4, 5, 6):
         assert B.lib.hlq_set_gemv_path(v) == 0
     for v in (0, 1, 2, 3, 4):
         assert B.lib.hlq_set_gemm_path(v) == 0
-    assert B.lib.hlq_set_gemv_path(3) == 3
+    assert B.lib.hlq_set_gemv_path(7) == 3
     assert B.lib.hlq_set_gemv_path(-1) == 3
     assert B.lib.hlq_set_gemm_path(5) == 3
     assert B.lib.hlq_set_gemv_path(0) == 0 and B.lib.hlq_set_gemm_path(0) == 0
