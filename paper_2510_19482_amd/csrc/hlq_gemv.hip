@@ -586,6 +586,7 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
         if (mx || !gemv_two_tiles_ok(q0, G0) || table_variant() >= 0) pl.TN = 1;
         const int maxw = mx ? hlq_gemv_mx_max_waves(q0, G0) : gemv_max_threads(q0, G0, pl.TN) / 64;
         if (pl.W > maxw) pl.W = maxw;
+        if (!mx && table_variant() >= 0 && pl.W > 8) pl.W = 8;   // the plain variant kernels: up to 512 lanes
         if (rowsk) {
             pl.W = 4;
             if (const int v = g_plan_w.load(std::memory_order_relaxed)) pl.W = v >= 8 ? 8 : v >= 4 ? 4 : 2;

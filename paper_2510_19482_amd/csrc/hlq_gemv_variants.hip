@@ -48,7 +48,7 @@ struct VRegs {
 constexpr int VAR_TABLE_BYTES = 2048;   // per wavefront, the largest form (32 tables x 16 fp32); the others use less
 
 template <int Q, int G, int V>
-__global__ void __launch_bounds__(1024)
+__global__ void __launch_bounds__(512)
 hlq_gemv_variant_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, const GemvProbs probs)
 {
     using Regs = VRegs<Q, G>;
@@ -281,7 +281,7 @@ hlq_status launch_q(int G, int variant, const GemvBatch &b, unsigned nblocks, in
 // per table.  The batch must be planned as for hlq_gemv_kernel with one tile per wavefront.
 hlq_status hlq_launch_gemv_variant(int variant, const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st)
 {
-    if (variant < 0 || variant > 3 || W < 1 || W > 16) return HLQ_ERR_UNSUPPORTED;
+    if (variant < 0 || variant > 3 || W < 1 || W > 8) return HLQ_ERR_UNSUPPORTED;
     switch (q) {
     case 1: return launch_q<1>(G, variant, b, nblocks, W, st);
     case 2: return launch_q<2>(G, variant, b, nblocks, W, st);
