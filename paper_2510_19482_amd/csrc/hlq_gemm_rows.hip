@@ -12,17 +12,19 @@
 // through their accumulator, and what comes out is the finished dot product of every row -- one scale
 // multiplication per (row, column, plane).  NT = 2 carries up to 8 rows, NT = 4 up to 16.
 //
-// Work split.  A workgroup of W wavefronts owns W adjacent column tiles (wavefront <-> tile, lane <->
-// column when loading, as in the GEMV kernels) and one K slice; every wavefront walks the slice on its
-// own -- after one barrier at the start nothing is shared, so the wavefronts of a SIMD drift apart and
-// one's vector phases (word transpose, activation conversion) run under the other's matrix-core phases.
-// Per chunk a wavefront converts the activations of all rows itself: a lane takes eight activations of
-// a row (four pairs of neighbours), cuts them into the four terms and writes two packed words per term
-// to its LDS block (matrix-core k order); the operands are read back once per chunk.  Per row a
-// power-of-two scale taken from the largest magnitude of the row's slice (found once per workgroup)
-// puts the activations high in the bf8 range; it is removed at the end.  K slices of different
-// workgroups meet in the workspace (partial sums, one arrival counter per tile, last arriver adds in
-// slice order).
+// Two kernels.  hlq_rows_split_kernel runs once per call: the workgroups of a (problem, activation row) find
+// the row's largest magnitude, which fixes a power-of-two scale that puts the row high in the bf8 range
+// (removed again at the end), cuts every activation into its four terms and writes them to the workspace
+// exactly as the matrix core wants its 8-bit operand: [chunk][operand][row][128 codes in matrix-core k
+// order] -- 2 KiB per operand and chunk, rows the call does not have as zeros.  hlq_gemm_rows_kernel then
+// has no activation work at all: a lane loads its 32 bytes of every operand straight into registers,
+// one chunk ahead.
+//
+// Work split of the main kernel.  A workgroup of W wavefronts owns W / kw adjacent column tiles and one
+// K slice; the kw wavefronts of a tile take consecutive runs of chunks and add their results through LDS
+// at the end (as in hlq_gemv_mx.hip); nothing is shared before that, so there is no barrier in the chunk
+// loop.  K slices of different workgroups meet in the workspace (partial sums, one arrival counter per
+// tile, the last arriver adds in slice order).
 #include "hlq_gemv_common.h"
 
 #ifndef HLQ_ROWS_DEBUG
@@ -39,19 +41,103 @@ typedef float float4v __attribute__((ext_vector_type(4)));
 typedef uint16_t __attribute__((may_alias)) u16_alias;
 typedef uint32_t __attribute__((may_alias)) u32_alias;
 
-constexpr int ROWS_XROW = 144;   // bytes per operand row in LDS: 128 codes + 16 of padding, so that the 16 rows a
-                                 // quarter-wave reads side by side fall into different banks
 constexpr int rows_meta_stride(int Q) { return ((Q + 1) * 2 + 7) & ~7; }
-constexpr int rows_xt_bytes(int NT) { return NT * 16 * ROWS_XROW; }   // NT operands x 16 rows
-// LDS per wavefront: operands | scales [64][stride] | row exponents (16 ints) | results [16][64] fp32
-constexpr int rows_wave_lds(int Q, int NT) { return rows_xt_bytes(NT) + 64 * rows_meta_stride(Q) + 64 + 16 * 64 * 4; }
-constexpr int rows_lds_bytes(int Q, int NT, int W) { return W * rows_wave_lds(Q, NT); }
+// LDS per wavefront: scales [64][stride] | results [16][64] fp32 for the sum over the tile's kw runs
+constexpr int rows_wave_lds(int Q) { return 64 * rows_meta_stride(Q) + 16 * 64 * 4; }
+constexpr int rows_lds_bytes(int Q, int W) { return W * rows_wave_lds(Q); }
+// bytes of one operand of one chunk in the workspace: 16 rows x 128 codes
+constexpr int ROWS_OPERAND_BYTES = 16 * 128;
 
 template <int CTRL, int ROWMASK = 0xf>
 __device__ __forceinline__ uint32_t max_dpp(uint32_t v)
 {
     const uint32_t moved = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROWMASK, 0xf, false);
     return max(v, moved);
+}
+
+// Workgroup = (activation row m = blockIdx.x, problem blockIdx.y, share blockIdx.z of the row's chunks).  Term t of row m goes to operand t / TPO,
+// operand row (t % TPO) * RPO + m; a row the call does not have is written as zeros.
+// Word cd = 8 gg + 2 rr + hh of an operand row holds the matrix-core k indices 32 gg + 8 rr + 4 hh + n, n = 0..3,
+// i.e. the activations k = 32 gg + 8 n + 2 rr + hh of the chunk: weight k0 = 2 p + hh of block gg is plane bit
+// p = 4 n + rr, which the plane expansion puts into nibble n + 4 hh of register rr.
+template <int NT>
+__global__ void __launch_bounds__(256) hlq_rows_split_kernel(const GemvProbs probs)
+{
+    constexpr int TPO = 4 / NT, RPO = 16 / TPO;
+    const GemvProb &P = probs.p[blockIdx.y];
+    const int m = (int)blockIdx.x, tid = (int)threadIdx.x;
+    const int K = P.nchunks * 128;
+    __shared__ uint32_t wmax[4];
+    const bool have = m < P.M;
+    const uint16_t *xrow = P.x + (size_t)min(m, P.M - 1) * P.ldx;
+
+    // ---- largest magnitude of the row (as an fp16 bit pattern; the ordering of magnitudes is that of the patterns).
+    // Every workgroup of the row scans the whole row (a few tens of KB): cheaper than a second launch or a hand-over.
+    uint32_t mxv = 0;
+    if (have) {
+        for (int k0 = 0; k0 < K; k0 += 256 * 8 * 8) {   // eight independent 128-bit loads in flight per thread
+            uint4 v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = k0 + (i * 256 + tid) * 8;
+                v[i] = k < K ? *(const uint4 *)(xrow + k) : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const uint32_t u[4] = {v[i].x, v[i].y, v[i].z, v[i].w};
+#pragma unroll
+                for (int d = 0; d < 4; ++d)
+                    mxv = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mxv),
+                                                                                __builtin_bit_cast(ushort2_t, u[d] & 0x7fff7fffu)));
+            }
+        }
+    }
+    mxv = max(mxv & 0xffffu, mxv >> 16);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mxv = max(mxv, (uint32_t)__shfl_xor((int)mxv, o));
+    if ((tid & 63) == 0) wmax[tid >> 6] = mxv;
+    __syncthreads();
+    mxv = max(max(wmax[0], wmax[1]), max(wmax[2], wmax[3]));
+    // biased fp16 exponent e of the largest magnitude: |x| < 2^(e-14); scaling by 2^(29-e) gives |x| < 2^15.  Plane
+    // codes are worth 1/2, 1, 2, 2 by expansion register rr: weights 1/2, 1/4, 1/8, 1/8 make every product
+    // bit x activation / 4.  The factor (<= 2^29) is applied as two fp16 multiplications.
+    const int e = (int)(mxv >> 10);
+    if (tid == 0 && m < RPO && blockIdx.z == 0) P.xexp[m] = e;
+
+    // ---- the terms: item = (chunk, word cd); this workgroup converts the chunks [c0, c1) of its row
+    const int per = (P.nchunks + (int)gridDim.z - 1) / (int)gridDim.z;
+    const int c0 = (int)blockIdx.z * per, c1 = min(c0 + per, P.nchunks);
+    for (int item = c0 * 32 + tid; item < c1 * 32; item += 256) {
+        const int ch = item >> 5, cd = item & 31;
+        const int rr = (cd >> 1) & 3;
+        char *dst = P.xt + (size_t)ch * (NT * ROWS_OPERAND_BYTES) + 4 * cd;
+        uint32_t word[4] = {0u, 0u, 0u, 0u};
+        if (have) {
+            const uint16_t *src = xrow + (size_t)ch * 128 + 32 * (cd >> 3) + 2 * rr + (cd & 1);
+            const uint32_t x0 = src[0], x1 = src[8], x2 = src[16], x3 = src[24];
+            const int k1 = (29 - e) / 2, k2 = (29 - e) - k1 - (rr == 0 ? 1 : rr == 1 ? 2 : 3);   // -4 <= k2 <= 14
+            const _Float16 f1 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k1) << 10));
+            const _Float16 f2 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k2) << 10));
+            const half2_t sw1 = {f1, f1}, sw2 = {f2, f2};
+            half2_t p0 = __builtin_bit_cast(half2_t, x0 | (x1 << 16));
+            half2_t p1 = __builtin_bit_cast(half2_t, x2 | (x3 << 16));
+            p0 = (p0 * sw1) * sw2;   // exact: powers of two, in range
+            p1 = (p1 * sw1) * sw2;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                // cut to three significant bits: the high byte of an fp16 is a bf8 code; the remainder is exact
+                const uint32_t u0 = __builtin_bit_cast(uint32_t, p0) & 0xff00ff00u, u1 = __builtin_bit_cast(uint32_t, p1) & 0xff00ff00u;
+                word[t] = __builtin_amdgcn_perm(u1, u0, 0x07050301u);   // the four codes in k order
+                p0 = p0 - __builtin_bit_cast(half2_t, u0);
+                p1 = p1 - __builtin_bit_cast(half2_t, u1);
+            }
+        }
+        if (m < RPO) {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+                *(u32_alias *)(dst + ((t / TPO) * 16 + (t % TPO) * RPO + m) * 128) = word[t];
+        }
+    }
 }
 
 template <int Q>
@@ -69,15 +155,10 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
     constexpr int TPO = 4 / NT;            // terms per operand
     constexpr int RPO = 16 / TPO;          // activation rows an operand carries
     constexpr int MSTR = rows_meta_stride(Q);
-    constexpr int XTB = rows_xt_bytes(NT);
     using Regs = RowsRegs<Q>;
     const int W = (int)(blockDim.x >> 6);
     extern __shared__ __attribute__((aligned(256))) char lds[];
 
-#ifdef HLQ_ROWS_TS
-    const long long ts0 = wall_clock64();
-    long long ts1 = 0, ts2 = 0, ts3 = 0;
-#endif
     const GemvProb P = probs.p[gemv_problem_of(bb_lo, bb_hi, (int)blockIdx.x)];
     int tg, slice;
     gemv_split_block(P, (int)blockIdx.x - P.blk_begin, tg, slice);
@@ -101,10 +182,8 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
     const int c = lane & 15, g = lane >> 4;
     const uint32_t moff = (uint32_t)(lane < tw ? lane : tw - 1) * 2u;   // clamped column: loads stay in bounds
     const uint32_t woff = moff * 8u;
-    char *xt = lds + wave * rows_wave_lds(Q, NT);        // this wavefront's operands [NT][16][ROWS_XROW],
-    char *meta = xt + XTB;                                // scales [64][MSTR],
-    int *exps = (int *)(meta + 64 * MSTR);                // row exponents [16]
-    float *red = (float *)(meta + 64 * MSTR + 64);        // and results [16][64] for the sum over the tile's KW runs
+    char *meta = lds + wave * rows_wave_lds(Q);           // this wavefront's scales [64][MSTR]
+    float *red = (float *)(meta + 64 * MSTR);             // and results [16][64] for the sum over the tile's KW runs
 
     // ---- weights: range-checked loads through a descriptor over [tile start, end of the run's last record) ----
     const uint32_t run_end = tile_ok ? hlq_rec_in_tile(tw, cend, Q, G) : 0u;
@@ -121,33 +200,7 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
         for (int r = 0; r <= Q; ++r) R.mt[r] = __builtin_amdgcn_raw_buffer_load_b16(wrsrc, (int)vo, tw * Q * 16 + r * tw * 2, 0);
     };
 
-    // ---- activations.  A conversion item is (row, 32-k block gg, register rr): the eight activations
-    // k = 32 gg + 8 n + 2 rr + hh (n = 0..3, hh = 0, 1), i.e. four pairs of neighbours, which end up as the two words
-    // cd = 8 gg + 2 rr + hh of the row -- matrix-core k indices 32 gg + 8 rr + 4 hh + n (weight k0 = 2 p + hh of block
-    // gg is plane bit p = 4 n + rr, which the expansion puts into nibble n + 4 hh of register rr).  Lane l takes
-    // items (row 4 i + (l >> 4), gg = (l >> 2) & 3, rr = l & 3), i < NIT: a row of sixteen lanes covers a chunk row.
-    constexpr int NIT = RPO / 4;
-    int rowexp[NIT];
-    const int rr = lane & 3, cw = 8 * ((lane >> 2) & 3) + 2 * rr;   // first of the item's two words
-    const uint32_t *xsrc[NIT];
-    bool conv_on[NIT];
-#pragma unroll
-    for (int i = 0; i < NIT; ++i) {
-        const int row = 4 * i + g;
-        conv_on[i] = row < M;
-        xsrc[i] = (const uint32_t *)(P.x + (size_t)min(row, M - 1) * P.ldx) + (16 * ((lane >> 2) & 3) + rr);
-    }
-    uint32_t xv[NIT][4];
-    auto load_x = [&](int ch) {
-        const int chx = max(min(ch, cend - 1), sbeg);   // stays inside the slice also for an empty run
-#pragma unroll
-        for (int i = 0; i < NIT; ++i)
-#pragma unroll
-            for (int n = 0; n < 4; ++n) xv[i][n] = xsrc[i][(size_t)chx * 64 + 4 * n];
-    };
-
-    // first loads: activations of the first chunk, then the weights of the first two chunks
-    load_x(cbeg);
+    // first loads: the weights of the first two chunks
     Regs R[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -156,97 +209,19 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
         load_meta(cbeg + i, R[i]);
     }
 
-    // clear the operand block (rows past M and the padding are never written)
-    for (int i = lane; i < XTB / 4; i += 64) ((uint32_t *)xt)[i] = 0u;
-
-    // ---- per row: largest magnitude of this wavefront's run -> power-of-two scale.  The sixteen lanes of a lane
-    // row scan an activation row, one 128-bit load per lane and chunk, eight chunks in flight.
-#pragma unroll
-    for (int i = 0; i < NIT; ++i) {
-        const int row = 4 * i + g;
-        const uint4 *xr = (const uint4 *)(P.x + (size_t)min(row, M - 1) * P.ldx) + c;
-        uint32_t mxv = 0;
-        for (int base = cbeg; base < cend; base += 8) {   // chunks past the end re-read the last one
-            uint4 v[8];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) v[k] = xr[(size_t)min(base + k, cend - 1) * 16];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                const uint32_t u[4] = {v[k].x, v[k].y, v[k].z, v[k].w};
-#pragma unroll
-                for (int d = 0; d < 4; ++d)
-                    mxv = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(ushort2_t, mxv),
-                                                                                __builtin_bit_cast(ushort2_t, u[d] & 0x7fff7fffu)));
-            }
-        }
-        mxv = max(mxv & 0xffffu, mxv >> 16);
-        mxv = max_dpp<0xB1>(mxv);          // quad_perm [1,0,3,2]
-        mxv = max_dpp<0x4E>(mxv);          // quad_perm [2,3,0,1]
-        mxv = max_dpp<0x124>(mxv);         // row_ror:4
-        mxv = max_dpp<0x128>(mxv);         // row_ror:8: every lane holds the maximum of its sixteen lanes = of its row
-        if (c == 0) exps[row] = (int)(mxv >> 10);   // for the lanes that hold this row's results at the end
-        rowexp[i] = (int)(mxv >> 10);
-    }
-    // biased fp16 exponent e of the largest magnitude: |x| < 2^(e-14); scaling by 2^(29-e) gives |x| < 2^15.  Plane
-    // codes are worth 1/2, 1, 2, 2 by expansion register rr: lane weights 1/2, 1/4, 1/8, 1/8 make every product
-    // bit x activation / 4.  The factor (<= 2^29) is applied as two fp16 multiplications.
-    half2_t sw1[NIT], sw2[NIT];
-#pragma unroll
-    for (int i = 0; i < NIT; ++i) {
-        const int e = rowexp[i];
-        const int k1 = (29 - e) / 2, k2 = (29 - e) - k1 - (rr == 0 ? 1 : rr == 1 ? 2 : 3);
-        const _Float16 f1 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k1) << 10));
-        const _Float16 f2 = __builtin_bit_cast(_Float16, (uint16_t)((15 + k2) << 10));
-        sw1[i] = (half2_t){f1, f1};
-        sw2[i] = (half2_t){f2, f2};
-    }
-
-    // Converts the activations in xv into their four terms and stores them in the operand block.  Term t of row m goes
-    // to operand t / TPO, operand row (t % TPO) * RPO + m.
-    auto convert = [&]() {
-#pragma unroll
-        for (int i = 0; i < NIT; ++i) {
-            if (!conv_on[i]) continue;
-            // xv[i][n] = (x[.. + 8 n + hh]) for hh = 0 (low half), 1 (high half): separate the two hh
-            half2_t p0[2], p1[2];
-            p0[0] = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(xv[i][1], xv[i][0], 0x05040100u));   // n = 0, 1, hh = 0
-            p1[0] = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(xv[i][3], xv[i][2], 0x05040100u));   // n = 2, 3, hh = 0
-            p0[1] = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(xv[i][1], xv[i][0], 0x07060302u));   // hh = 1
-            p1[1] = __builtin_bit_cast(half2_t, __builtin_amdgcn_perm(xv[i][3], xv[i][2], 0x07060302u));
-            char *dst = xt + (4 * i + g) * ROWS_XROW + 4 * cw;
-#pragma unroll
-            for (int hh = 0; hh < 2; ++hh) {
-                p0[hh] = (p0[hh] * sw1[i]) * sw2[i];   // exact: powers of two, in range
-                p1[hh] = (p1[hh] * sw1[i]) * sw2[i];
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                uint32_t word[2];
-#pragma unroll
-                for (int hh = 0; hh < 2; ++hh) {
-                    const uint32_t u0 = __builtin_bit_cast(uint32_t, p0[hh]) & 0xff00ff00u;
-                    const uint32_t u1 = __builtin_bit_cast(uint32_t, p1[hh]) & 0xff00ff00u;
-                    word[hh] = __builtin_amdgcn_perm(u1, u0, 0x07050301u);   // the four codes (high bytes) in k order
-                    if (t < 3) {
-                        p0[hh] = p0[hh] - __builtin_bit_cast(half2_t, u0);   // exact remainders
-                        p1[hh] = p1[hh] - __builtin_bit_cast(half2_t, u1);
-                    }
-                }
-                *(uint2v *)(dst + ((t / TPO) * 16 + (t % TPO) * RPO) * ROWS_XROW) = (uint2v){word[0], word[1]};
-            }
-        }
-    };
-
-    // ---- operand role: row (lane & 15) of every operand, 16-k runs [16 g, 16 g + 16) and [64 + 16 g, ...) ----------
-    const char *a_src = xt + (lane & 15) * ROWS_XROW + 16 * g;
+    // ---- activation operands: made by hlq_rows_split_kernel, [chunk][operand][row][128 codes].  Lane (row = lane & 15,
+    // g) holds the 16-k runs [16 g, 16 g + 16) and [64 + 16 g, ...) of its row: two 128-bit loads per operand.
+    const char *a_src = P.xt + (lane & 15) * 128 + 16 * g;
     struct Ops {
         int8v A[NT];
     };
-    auto read_ops = [&](Ops &o) {
+    auto load_ops = [&](int ch, Ops &o) {
+        const int chx = max(min(ch, cend - 1), sbeg);   // stays inside K also past the end of the run
+        const char *src = a_src + (size_t)chx * (NT * ROWS_OPERAND_BYTES);
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
-            const uint4 lo = *(const uint4 *)(a_src + t * 16 * ROWS_XROW);
-            const uint4 hi = *(const uint4 *)(a_src + t * 16 * ROWS_XROW + 64);
+            const uint4 lo = *(const uint4 *)(src + t * ROWS_OPERAND_BYTES);
+            const uint4 hi = *(const uint4 *)(src + t * ROWS_OPERAND_BYTES + 64);
             o.A[t] = (int8v){(int)lo.x, (int)lo.y, (int)lo.z, (int)lo.w, (int)hi.x, (int)hi.y, (int)hi.z, (int)hi.w};
         }
     };
@@ -360,50 +335,28 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
         for (int cb = 0; cb < 4; ++cb) apply(xs, cb, Q);
     };
 
-    // ---- chunk loop: no barrier; LDS operations of a wavefront execute in order, so the conversion of the next chunk
-    // may overwrite the operand block as soon as this chunk's operands have been asked for -------------------------
-    convert();                  // chunk cbeg
-    load_x(cbeg + 1);
+    // ---- chunk loop: no barrier; weights two chunks ahead, activation operands and staged scales one chunk ahead -----
+    Ops oA, oB;
+    load_ops(cbeg, oA);
     Sc sc0, sc1;
     stage_scales(R[0], sc0);
-#ifdef HLQ_ROWS_TS
-    ts1 = wall_clock64();
-#endif
     for (int ch = cbeg; ch < cend; ch += 2) {   // two chunks per trip: register sets are named at compile time
-#ifdef HLQ_ROWS_TS
-        if (ch == cbeg + 2) ts2 = wall_clock64();
-#endif
-        {
-            Ops o;
-            read_ops(o);
-            convert();          // next chunk's operands (xv holds its activations)
-            load_x(ch + 2);
-            stage_scales(R[1], sc1);
-            step(R[0], o, sc0, ch + 2);
-        }
+        load_ops(ch + 1, oB);
+        stage_scales(R[1], sc1);
+        step(R[0], oA, sc0, ch + 2);
         if (ch + 1 < cend) {
-            Ops o;
-            read_ops(o);
-            convert();
-            load_x(ch + 3);
+            load_ops(ch + 2, oA);
             stage_scales(R[0], sc0);
-            step(R[1], o, sc1, ch + 3);
+            step(R[1], oB, sc1, ch + 3);
         }
     }
 
-#ifdef HLQ_ROWS_TS
-    ts3 = wall_clock64();
-    if (threadIdx.x == 0 && blockIdx.x < 1000) {
-        long long *t = (long long *)((char *)probs.p[0].cnt + 65536) + 8 * blockIdx.x;
-        t[0] = ts0; t[1] = ts1; t[2] = ts2; t[3] = ts3; t[5] = cend - cbeg; t[6] = (long long)(&P.cnt[0] - probs.p[0].cnt);
-    }
-#endif
     // ---- undo the rows' scaling, add the two term halves (NT = 2) and the tile's KW runs, store --------------------
     float y[4][4];
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) {
         const int row = (NT == 2 ? 4 * (g & 1) : 4 * g) + sl;
-        const float f = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + exps[row]) << 23);   // 4 * 2^(e-29)
+        const float f = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + P.xexp[row]) << 23);   // 4 * 2^(e-29)
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
             float v = acc[sl][cb];
@@ -418,7 +371,7 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
             for (int cb = 0; cb < 4; ++cb) red[(sl * 4 + cb) * 64 + lane] = y[sl][cb];
         __syncthreads();
         if (part == 0) {
-            constexpr int RSTR = rows_wave_lds(Q, NT) / 4;   // floats between wavefronts' blocks
+            constexpr int RSTR = rows_wave_lds(Q) / 4;   // floats between wavefronts' blocks
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl)
 #pragma unroll
@@ -426,9 +379,6 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
                     for (int w2 = 1; w2 < KW; ++w2) y[sl][cb] += red[w2 * RSTR + (sl * 4 + cb) * 64 + lane];
         }
     }
-#ifdef HLQ_ROWS_TS
-    if (threadIdx.x == 0 && blockIdx.x < 1000) ((long long *)((char *)probs.p[0].cnt + 65536))[8 * blockIdx.x + 4] = wall_clock64();
-#endif
     if (!tile_ok || part != 0) return;
     if (NT == 2 && g >= 2) return;
     const int row0 = (NT == 2 ? 4 * (g & 1) : 4 * g);
@@ -507,10 +457,13 @@ void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int rows, hipStream_
     const dim3 blk(64 * W);
     const GemvKernelArgs a = gemv_kernel_args(b);
     if constexpr (G >= 128) {
-        if (rows <= 8)
-            hlq_gemm_rows_kernel<Q, G, 2><<<nblocks, blk, (size_t)rows_lds_bytes(Q, 2, W), st>>>(a.lo, a.hi, a.out_f32, a.probs);
-        else
-            hlq_gemm_rows_kernel<Q, G, 4><<<nblocks, blk, (size_t)rows_lds_bytes(Q, 4, W), st>>>(a.lo, a.hi, a.out_f32, a.probs);
+        if (rows <= 8) {
+            hlq_rows_split_kernel<2><<<dim3(8, b.count, 8), 256, 0, st>>>(a.probs);
+            hlq_gemm_rows_kernel<Q, G, 2><<<nblocks, blk, (size_t)rows_lds_bytes(Q, W), st>>>(a.lo, a.hi, a.out_f32, a.probs);
+        } else {
+            hlq_rows_split_kernel<4><<<dim3(16, b.count, 8), 256, 0, st>>>(a.probs);
+            hlq_gemm_rows_kernel<Q, G, 4><<<nblocks, blk, (size_t)rows_lds_bytes(Q, W), st>>>(a.lo, a.hi, a.out_f32, a.probs);
+        }
     }
 }
 
@@ -525,6 +478,13 @@ hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, int rows
 }
 
 } // namespace
+
+size_t hlq_gemm_rows_xt_bytes(const HlqDims &dm, int64_t M)
+{
+    if (M < 1 || M > hlq_gemm_rows_max(dm.G)) return 0;
+    const size_t nt = M <= 8 ? 2 : 4;
+    return (size_t)dm.nchunks * nt * ROWS_OPERAND_BYTES + 256;   // operands + the row exponents, kept 256-byte aligned
+}
 
 // rows this kernel carries for group size G (0: no instantiation)
 int hlq_gemm_rows_max(int G) { return G >= 128 ? 16 : 0; }

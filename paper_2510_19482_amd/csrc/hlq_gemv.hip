@@ -571,7 +571,7 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
         pl.W = 4;
         // chunks per K slice: long enough that the partial sums (rows x columns x slices) stay a small part of the
         // traffic, short enough that the launch has several workgroups per compute unit
-        pl.cpw = units < 12000 ? 4 : 8;
+        pl.cpw = units < 12000 ? 4 : 16;   // measured on the 8B layer at q = 4: 16 beats 8 (one round of workgroups instead of two)
         if (const int v = g_plan_cpw.load(std::memory_order_relaxed)) pl.cpw = v < 4 ? 4 : v;
     } else if (rows > 1) {
         // measured (8B shapes, q = 4, M = 2..8): short runs on few wavefronts per workgroup for narrow
@@ -654,6 +654,22 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
         if (p.nslices > 1) {
             cnt_used += mx ? dm.ntiles : p.ntg;
             part += (size_t)p.nslices * dm.N * rows;
+        }
+    }
+    if (rowsk) {
+        // behind all partial sums: every problem's activations in operand form, then its row exponents
+        char *xt = (char *)(((uintptr_t)part + 255u) & ~(uintptr_t)255u);
+        for (int i = 0; i < count; ++i) {
+            const size_t nb = hlq_gemm_rows_xt_bytes(items[order[i]].dm, rows);
+            b.p[i].xt = xt;
+            b.p[i].xexp = (int *)(xt + nb - 256);
+            xt += nb;
+        }
+        part = (float *)xt;
+    } else {
+        for (int i = 0; i < count; ++i) {
+            b.p[i].xt = nullptr;
+            b.p[i].xexp = nullptr;
         }
     }
     for (int i = count; i < HLQ_MAX_BATCH; ++i) {
@@ -780,7 +796,8 @@ size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M)
 {
     const int cap = hlq_gemm_mx_rows_per_pass(dm.G);
     const int64_t rows = M < cap ? M : cap;
-    return (size_t)rows * hlq_gemv_partial_bytes(dm);   // slices are never shorter than 4 chunks here either
+    // slices are never shorter than 4 chunks here either; the many-rows kernel adds the operand form of the activations
+    return (size_t)rows * hlq_gemv_partial_bytes(dm) + hlq_gemm_rows_xt_bytes(dm, 16) + 256;
 }
 
 // Y[M, N] = X[M, K] @ W^ for as many rows as one pass of the matrix-core GEMV kernel carries.

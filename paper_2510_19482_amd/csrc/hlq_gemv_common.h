@@ -19,6 +19,8 @@ struct GemvProb {
     unsigned slice_magic;   // ceil(2^32 / nslices) for nslices > 1: local / nslices = umulhi(local, slice_magic)
     int M;             // matrix-core kernel, batched rows: activation rows; x / y row strides in elements
     long ldx, ldy;
+    char *xt;          // many-rows kernel: the activations as matrix-core operands [chunk][operand][16 rows][128] (workspace)
+    int *xexp;         //                   and the exponent of every row's scale [16]
 };
 
 // Host-side description of a launch.
@@ -88,3 +90,7 @@ int hlq_gemm_rows_max(int G);
 
 // table-storage variants of the lookup formulation (hlq_gemv_variants.hip); batch planned as for hlq_gemv_kernel, TN = 1
 hlq_status hlq_launch_gemv_variant(int variant, const GemvBatch &b, unsigned nblocks, int W, int q, int G, hipStream_t st);
+
+// workspace bytes the many-rows kernel needs beyond the partial sums, for one problem with M rows: the operand
+// form of the activations and the row exponents (0 if M rows do not go to that kernel)
+size_t hlq_gemm_rows_xt_bytes(const HlqDims &dm, int64_t M);
