@@ -18,7 +18,8 @@ __device__ __forceinline__ float half_bits_to_float(uint16_t h) { return (float)
 __global__ void __launch_bounds__(64)
 hlq_gemm_safe_kernel(const HlqSafeProbs pr, const int M, const int out_f32, int *flag, int *done)
 {
-    if (__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0) return;
+    // an ordinary load: the flag was written by the launch before this one, and a kernel boundary makes that visible
+    if (*(const int *)flag == 0) return;
     const int lane = threadIdx.x;
     for (long item = blockIdx.x; item < pr.items_total; item += gridDim.x) {
         int pi = 0;
@@ -110,7 +111,8 @@ hlq_status hlq_launch_gemm_safe(int count, const HlqGemvItem *items, int64_t M, 
     for (int i = count; i < HLQ_MAX_BATCH; ++i) pr.p[i] = pr.p[0];
     pr.count = count;
     pr.items_total = total;
-    const unsigned grid = (unsigned)(total < 2048 ? total : 2048);
+    // few workgroups: in the normal case all of them only look at the flag and leave, and that costs per workgroup
+    const unsigned grid = (unsigned)(total < 512 ? total : 512);
     hlq_gemm_safe_kernel<<<grid, 64, 0, st>>>(pr, (int)M, out == HLQ_OUT_F32, hlq_ws_range_flag(ws), hlq_ws_range_flag(ws) + 1);
     return HLQ_OK;
 }
