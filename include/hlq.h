@@ -266,6 +266,18 @@ HLQ_API hlq_status hlq_stream_read(const void *src, size_t bytes, int blocks, vo
 HLQ_API hlq_status hlq_stream_read_shaped(const void *src, size_t bytes, int blocks, int unroll, int temporal,
                                           void *sink, size_t sink_bytes, void *stream);
 
+/* Measurement helper, no part of the method: a loop of nothing but the fp16 matrix-core instruction the
+ * tiled prefill kernel uses (v_mfma_f32_32x32x16_f16) on register operands.  `blocks` workgroups of four
+ * wavefronts each load four operand pairs from `operands` (fp16 values, device, 16-byte aligned,
+ * operand_bytes a multiple of 16, between 16 bytes and 1 GiB, else HLQ_ERR_BAD_STRIDE; wavefronts take
+ * successive 1 KiB units, wrapping around) and issue 16 * iters matrix-core instructions per
+ * wavefront; one float per lane goes to `sink` (sink_bytes >= blocks * 1024, else
+ * HLQ_ERR_BUFFER_TOO_SMALL).  *flop (host, may be NULL) receives the floating-point operations of the
+ * launch.  1 <= iters <= 2^20, 1 <= blocks <= 65536 (else HLQ_ERR_UNSUPPORTED).  Benchmarks time it with
+ * constant and with random operand data as the matrix-core ceiling beside the prefill GEMM. */
+HLQ_API hlq_status hlq_mfma_probe(const void *operands, size_t operand_bytes, int iters, int blocks, void *sink,
+                                  size_t sink_bytes, double *flop, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

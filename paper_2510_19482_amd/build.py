@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libhlq.so")
-SOURCES = ["hlq_api.hip", "hlq_pack.hip", "hlq_quantize.hip", "hlq_gemv.hip", "hlq_gemv_mx.hip", "hlq_gemv_variants.hip", "hlq_gemm_rows.hip", "hlq_gemm.hip", "hlq_gemm_mfma.hip", "hlq_gemm_safe.hip", "hlq_stream_read.hip", "hlq_static_scratch.hip"]
+SOURCES = ["hlq_api.hip", "hlq_pack.hip", "hlq_quantize.hip", "hlq_gemv.hip", "hlq_gemv_mx.hip", "hlq_gemv_variants.hip", "hlq_gemm_rows.hip", "hlq_gemm.hip", "hlq_gemm_mfma.hip", "hlq_gemm_safe.hip", "hlq_stream_read.hip", "hlq_mfma_probe.hip", "hlq_static_scratch.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

@@ -100,6 +100,19 @@ def test_stream_read_argument_errors_launch_nothing():
     assert B.lib.hlq_stream_read(fake, 0, 0, fake, 0, None) == 0            # nothing to read
 
 
+def test_mfma_probe_argument_errors_launch_nothing():
+    fake = 0x1000
+    assert B.lib.hlq_mfma_probe(None, 4096, 1, 1, fake, 1024, None, None) == 1
+    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 1, None, 1024, None, None) == 1
+    assert B.lib.hlq_mfma_probe(fake + 8, 4096, 1, 1, fake, 1024, None, None) == 5
+    assert B.lib.hlq_mfma_probe(fake, 4100, 1, 1, fake, 1024, None, None) == 5
+    assert B.lib.hlq_mfma_probe(fake, 0, 1, 1, fake, 1024, None, None) == 5
+    assert B.lib.hlq_mfma_probe(fake, 4096, 0, 1, fake, 1024, None, None) == 3
+    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 0, fake, 1024, None, None) == 3
+    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 65537, fake, 1 << 30, None, None) == 3
+    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 2, fake, 2047, None, None) == 4
+
+
 def test_workspace_sizes_cover_every_path():
     # counters + room for split-K partial sums: K is never cut into slices shorter than four chunks,
     # so (K/128 + 3) // 4 slices of N fp32 values bound every GEMV plan; a few-rows GEMM needs that

@@ -48,3 +48,32 @@ def test_shaped_read_rejects_other_unrolls():
     with pytest.raises(B.HlqError) as e:
         B.hlq_stream_read_shaped(buf, 4096, buf, unroll=3)
     assert e.value.status == 3
+
+
+def test_mfma_probe_sums_what_its_operands_say():
+    # hlq_mfma_probe (measurement helper): with small-integer operands every product and sum is exact, and the sum
+    # of all elements of A B is sum_k (column sum of A)[k] (row sum of B)[k], whatever the order inside the
+    # matrix core.  Lane l of a 32x32x16 operand holds row / column l % 32 and k = 8 (l / 32) .. + 7.
+    iters, blocks = 3, 5
+    print("mfma_probe", iters, blocks, flush=True)
+    rng = np.random.default_rng(7)
+    waves = blocks * 4
+    units = waves * 8 - 3                      # fewer units than the wavefronts ask for: indices wrap around
+    host = rng.integers(-2, 3, size=(units, 64, 8)).astype(np.float16)
+    ops = torch.from_numpy(host).cuda()
+    sink = torch.zeros(blocks * 256, dtype=torch.float32, device="cuda")
+    flop = B.hlq_mfma_probe(ops, iters, blocks, sink)
+    torch.cuda.synchronize()
+    assert flop == waves * iters * 16 * 2.0 * 32 * 32 * 16
+    got = sink.cpu().numpy().astype(np.float64).reshape(waves, 64).sum(axis=1)
+    flat = host.astype(np.float64).reshape(-1, 8)      # 16-byte units as the kernel indexes them
+    nflat = flat.shape[0]
+
+    def ksums(w, slot):
+        idx = ((w * 8 + slot) * 64 + np.arange(64)) % nflat
+        return flat[idx].reshape(2, 32, 8).sum(axis=1).reshape(16)   # sum over the 32 rows / columns, per k
+    for w in range(waves):
+        a = [ksums(w, 2 * o) for o in range(4)]
+        b = [ksums(w, 2 * o + 1) for o in range(4)]
+        want = iters * sum(float(a[(o + c) % 4] @ b[o]) for o in range(4) for c in range(4))
+        assert got[w] == want, (w, got[w], want)
