@@ -225,7 +225,9 @@ HLQ_API hlq_status hlq_gemv_plan_query(int count, const hlq_desc *descs, int64_t
 HLQ_API hlq_status hlq_set_gemv_path(int path);
 
 /* Tuning knob (process-wide, atomic): formulation used by hlq_lut_gemm for M > 1.
- * 0 = automatic (matrix cores from M = 2 on, the measured crossover),
+ * 0 = automatic (matrix cores from M = 2 on: the lookup kernel for M > 1 is a plain first version --
+ *     tables shared per workgroup, two barriers per step -- and is kept as the method's own formulation
+ *     for reference, not as a tuned competitor),
  * 1 = table lookups always,
  * 2 = matrix cores always: for a few rows (M <= 4 at G >= 128, <= 2 at G = 64, 1 at G = 32) the
  *     GEMV kernel of hlq_set_gemv_path(2) with several activation rows per operand, above that
@@ -240,7 +242,8 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
 HLQ_API hlq_status hlq_set_gemm_path(int path);
 
 /* Y[M, N] = X[M, K] @ W^  (same procedure with one table set per row, the decoded
- * weight words shared by all rows; from the measured crossover in M on, the same product is
+ * weight words shared by all rows; by default, from M = 2 on, the per-plane products run on the
+ * matrix cores, and from a few rows on the same product is
  * computed as a dense contraction on the matrix cores with W^ rebuilt tile by tile in
  * registers -- see hlq_set_gemm_path).  X row-major with leading dimension ldx >= K (in
  * elements), Y row-major with ldy >= N.  M = 0 is a no-op.
