@@ -234,8 +234,10 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
  *     the tiled kernel that rebuilds W^ in fp16 registers (hlq_lut_gemm_batch keeps up to twice
  *     as many rows on the GEMV kernel, where one launch for several problems pays),
  * 3 = as 2 but never the few-rows GEMV kernel,
- * 4 = as 2, and hlq_lut_gemm_batch keeps up to 16 rows (G >= 128) on the many-rows kernel, which by
- *     default takes 5..8 rows only.
+ * 4 = as 2, and hlq_lut_gemm_batch keeps up to 16 rows (G >= 128) on the many-rows kernel whatever the size of
+ *     the launch (by default it takes 5..8 rows always and 9..16 rows when the launch has at least 2400
+ *     chunk-tiles of 64 columns x 128 k, e.g. two 4096 x 4096 matrices; smaller launches of 9..16 rows
+ *     go to the tiled kernel).
  * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel represents scales up to |s_j| < 512 (and
  * zeros of that size); it checks what it loads, and a call whose weights lie outside is computed again
  * by an fp32 kernel launched behind it (slow, but right for every finite fp16 parameter). */
@@ -269,16 +271,20 @@ HLQ_API hlq_status hlq_stream_read(const void *src, size_t bytes, int blocks, vo
 HLQ_API hlq_status hlq_stream_read_shaped(const void *src, size_t bytes, int blocks, int unroll, int temporal,
                                           void *sink, size_t sink_bytes, void *stream);
 
-/* Measurement helper, no part of the method: a loop of nothing but the fp16 matrix-core instruction the
- * tiled prefill kernel uses (v_mfma_f32_32x32x16_f16) on register operands.  `blocks` workgroups of four
- * wavefronts each load four operand pairs from `operands` (fp16 values, device, 16-byte aligned,
- * operand_bytes a multiple of 16, between 16 bytes and 1 GiB, else HLQ_ERR_BAD_STRIDE; wavefronts take
- * successive 1 KiB units, wrapping around) and issue 16 * iters matrix-core instructions per
- * wavefront; one float per lane goes to `sink` (sink_bytes >= blocks * 1024, else
+/* Measurement helper, no part of the method: a loop of nothing but one matrix-core instruction on register
+ * operands.  kind 0: the fp16 instruction the tiled prefill kernel uses (v_mfma_f32_32x32x16_f16), 16 * iters
+ * instructions per wavefront in four accumulator chains; kind 1: the 8-bit x 4-bit instruction of the bit-plane
+ * GEMV kernels (v_mfma_f32_16x16x128_f8f6f4 with bf8 and fp4 operands), 32 * iters instructions per wavefront in
+ * eight chains; other kinds HLQ_ERR_UNSUPPORTED.  `blocks` workgroups of four
+ * wavefronts each load four operand sets from `operands` (device, 16-byte aligned,
+ * operand_bytes a multiple of 16, between 16 bytes and 1 GiB, else HLQ_ERR_BAD_STRIDE; fp16 values for kind 0,
+ * any bytes for kind 1, where the top exponent bit of every bf8 code is cleared; wavefronts take
+ * successive 1 KiB units, wrapping around);
+ * one float per lane goes to `sink` (sink_bytes >= blocks * 1024, else
  * HLQ_ERR_BUFFER_TOO_SMALL).  *flop (host, may be NULL) receives the floating-point operations of the
  * launch.  1 <= iters <= 2^20, 1 <= blocks <= 65536 (else HLQ_ERR_UNSUPPORTED).  Benchmarks time it with
  * constant and with random operand data as the matrix-core ceiling beside the prefill GEMM. */
-HLQ_API hlq_status hlq_mfma_probe(const void *operands, size_t operand_bytes, int iters, int blocks, void *sink,
+HLQ_API hlq_status hlq_mfma_probe(int kind, const void *operands, size_t operand_bytes, int iters, int blocks, void *sink,
                                   size_t sink_bytes, double *flop, void *stream);
 
 #ifdef __cplusplus

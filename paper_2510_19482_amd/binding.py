@@ -88,7 +88,7 @@ def _load() -> ctypes.CDLL:
     lib.hlq_stream_read.restype = ctypes.c_int
     lib.hlq_stream_read.argtypes = [vp, sz, ctypes.c_int, vp, sz, vp]
     lib.hlq_mfma_probe.restype = ctypes.c_int
-    lib.hlq_mfma_probe.argtypes = [vp, sz, ctypes.c_int, ctypes.c_int, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
+    lib.hlq_mfma_probe.argtypes = [ctypes.c_int, vp, sz, ctypes.c_int, ctypes.c_int, vp, sz, ctypes.POINTER(ctypes.c_double), vp]
     lib.hlq_stream_read_shaped.restype = ctypes.c_int
     lib.hlq_stream_read_shaped.argtypes = [vp, sz, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, sz, vp]
     lib.hlq_lut_gemm.restype = ctypes.c_int
@@ -242,10 +242,11 @@ def hlq_stream_read_shaped(src, nbytes: int, sink, blocks: int = 0, unroll: int 
                                                                 _stream_ptr(stream)))
 
 
-def hlq_mfma_probe(operands, iters: int, blocks: int, sink, stream=None) -> float:
-    """Launch the matrix-core-only measurement loop; returns the floating-point operations of the launch."""
+def hlq_mfma_probe(operands, iters: int, blocks: int, sink, kind: int = 0, stream=None) -> float:
+    """Launch the matrix-core-only measurement loop (kind 0: fp16 32x32x16, 1: bf8 x fp4 16x16x128); returns the
+    floating-point operations of the launch."""
     flop = ctypes.c_double(0.0)
-    _check("hlq_mfma_probe", lib.hlq_mfma_probe(_ptr(operands), operands.numel() * operands.element_size(), iters, blocks,
+    _check("hlq_mfma_probe", lib.hlq_mfma_probe(kind, _ptr(operands), operands.numel() * operands.element_size(), iters, blocks,
                                                 _ptr(sink), sink.numel() * sink.element_size(), ctypes.byref(flop),
                                                 _stream_ptr(stream)))
     return flop.value

@@ -268,7 +268,7 @@ hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const void *cons
     }
     if (ws_bytes < need) return HLQ_ERR_BUFFER_TOO_SMALL;
     // one launch when the few-rows kernel carries M rows and the lookup formulation is not forced
-    if (M == 1 || (M <= hlq_gemm_mx_rows_per_pass(items[0].dm.G) && hlq_gemm_uses_mx_rows(M)))
+    if (M == 1 || (hlq_gemm_batch_on_mx(count, items, M) && hlq_gemm_uses_mx_rows(M)))
         return hlq_launch_gemv_batch(count, items, out, ws, (hipStream_t)stream);
     // more rows on the matrix cores: one launch of the tiled kernel over all problems (and one for the partial
     // sums where K is split)

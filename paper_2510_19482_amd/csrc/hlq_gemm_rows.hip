@@ -27,8 +27,11 @@
 // tile, the last arriver adds in slice order).
 #include "hlq_gemv_common.h"
 
+#ifndef HLQ_ROWS_SKIP
+#define HLQ_ROWS_SKIP 0    // timing experiments (wrong results), bit mask -- 1: no scale multiplications, 2: no word transpose, 4: no plane expansion
+#endif
 #ifndef HLQ_ROWS_DEBUG
-#define HLQ_ROWS_DEBUG 0   // timing experiments -- 1: loads only (no matrix-core work), 2: no reloads (compute only)
+#define HLQ_ROWS_DEBUG 0   // timing experiments -- 1: loads only (no matrix-core work), 2: no weight reloads (compute only), 3: nor operand reloads
 #endif
 
 namespace {
@@ -216,6 +219,7 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
         int8v A[NT];
     };
     auto load_ops = [&](int ch, Ops &o) {
+        if (HLQ_ROWS_DEBUG == 3 && ch > cbeg + 1) return;   // timing experiment: operands of the first two chunks only
         const int chx = max(min(ch, cend - 1), sbeg);   // stays inside K also past the end of the run
         const char *src = a_src + (size_t)chx * (NT * ROWS_OPERAND_BYTES);
 #pragma unroll
@@ -242,6 +246,7 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
         return (float)((i & 1) ? h.y : h.x);
     };
     auto expand = [](uint32_t w) -> int8v {   // plane word -> 32 fp4 codes (bit 4p+r -> nibble p of register r)
+        if (HLQ_ROWS_SKIP & 4) return (int8v){(int)w, 0x22222222, 0x44444444, 0x11111111, 0, 0, 0, 0};
         return (int8v){(int)(w & 0x11111111u), (int)(w & 0x22222222u), (int)(w & 0x44444444u),
                        (int)((w >> 1) & 0x44444444u), 0, 0, 0, 0};
     };
@@ -276,6 +281,10 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
             return;
         }
         auto apply = [&](const float4v &d, int cb, int which) {
+            if (HLQ_ROWS_SKIP & 1) {
+                acc[0][cb] += d[which & 3];
+                return;
+            }
             const float sc = scale_of(s.m[cb], which);
 #pragma unroll
             for (int sl = 0; sl < 4; ++sl) acc[sl][cb] += sc * d[sl];
@@ -290,8 +299,9 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
             const uint2v t02 = __builtin_amdgcn_permlane32_swap(s01.x, s23.x, false, false);
             const uint2v t13 = __builtin_amdgcn_permlane32_swap(s01.y, s23.y, false, false);
             wt[j][0] = t02.x; wt[j][2] = t02.y; wt[j][1] = t13.x; wt[j][3] = t13.y;
+            if (HLQ_ROWS_SKIP & 2) { wt[j][0] = R.w[j][0]; wt[j][1] = R.w[j][1]; wt[j][2] = R.w[j][2]; wt[j][3] = R.w[j][3]; }
         }
-        if (HLQ_ROWS_DEBUG != 2) load_meta(ch_reload, R);             // its scales were staged one chunk ahead
+        if (HLQ_ROWS_DEBUG < 2) load_meta(ch_reload, R);             // its scales were staged one chunk ahead
         // Items go through the matrix core two at a time: the chains of a pair are independent, so the second
         // instruction of one never waits for the first of the same chain, and the vector work of the stage (expansion
         // of the next pair's words, scales on the previous pair's results) is dealt out between the matrix-core
@@ -315,7 +325,7 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
                 nB0 = expand(wt[(n0 + 2) / 4][(n0 + 2) % 4]);
                 nB1 = expand(wt[(n1 + 2) / 4][(n1 + 2) % 4]);
             }
-            if (n1 % 4 == 3 && HLQ_ROWS_DEBUG != 2) load_plane(ch_reload, R, n1 / 4);   // the plane's last item is in this pair
+            if (n1 % 4 == 3 && HLQ_ROWS_DEBUG < 2) load_plane(ch_reload, R, n1 / 4);   // the plane's last item is in this pair
             if (pr >= 1) {
                 apply(pA, (n0 - 2) % 4, (n0 - 2) / 4);
                 apply(pB, (n1 - 2) % 4, (n1 - 2) / 4);

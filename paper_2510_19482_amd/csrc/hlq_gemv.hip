@@ -781,15 +781,28 @@ hlq_status hlq_gemv_plan_describe(int count, const HlqDims *dms, int M, hlq_gemv
     return HLQ_OK;
 }
 
-// Rows an MX launch can carry for group size G (two row sets).
+// Rows an MX launch can carry for group size G: two row sets of the GEMV kernel, or what the many-rows kernel holds.
 int hlq_gemm_mx_rows_per_pass(int G)
 {
-    // the many-rows kernel carries 16 rows, but from 9 rows on (four chained operands per item) one launch of the
-    // tiled kernel is faster on the measured shapes: by default it takes up to 8 rows, with hlq_set_gemm_path(4) all 16
     const int two_sets = 2 * hlq_gemv_mx_rows_per_set(G);
-    int many = hlq_gemm_rows_max(G);
-    if (many > 8 && !hlq_gemm_rows_all()) many = 8;
+    const int many = hlq_gemm_rows_max(G);
     return many > two_sets ? many : two_sets;
+}
+
+// Whether a grouped launch of M rows goes to the matrix-core GEMV-shaped kernels (few-rows / many-rows) rather
+// than to the tiled kernel.  Up to 8 rows always (where a pass carries them).  9..16 rows (four chained operands per
+// item in the many-rows kernel): measured on 8B-layer shapes at q = 2..4, the many-rows kernel wins once the launch
+// has a few thousand chunk-tiles (whole layer at q = 4: 60 against 69 us; two small problems: 18 against 20 us),
+// the tiled kernel on a single 4096 x 4096 (16 against 18 us); hlq_set_gemm_path(4) sends all of them here.
+bool hlq_gemm_batch_on_mx(int count, const HlqGemvItem *items, int64_t M)
+{
+    if (count < 1 || M < 1) return false;
+    const int G = items[0].dm.G;
+    if (M > hlq_gemm_mx_rows_per_pass(G)) return false;
+    if (M <= 8 || hlq_gemm_rows_all()) return true;
+    long units = 0;
+    for (int i = 0; i < count; ++i) units += (long)items[i].dm.ntiles * items[i].dm.nchunks;
+    return units >= 2400;
 }
 
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M)

@@ -102,15 +102,17 @@ def test_stream_read_argument_errors_launch_nothing():
 
 def test_mfma_probe_argument_errors_launch_nothing():
     fake = 0x1000
-    assert B.lib.hlq_mfma_probe(None, 4096, 1, 1, fake, 1024, None, None) == 1
-    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 1, None, 1024, None, None) == 1
-    assert B.lib.hlq_mfma_probe(fake + 8, 4096, 1, 1, fake, 1024, None, None) == 5
-    assert B.lib.hlq_mfma_probe(fake, 4100, 1, 1, fake, 1024, None, None) == 5
-    assert B.lib.hlq_mfma_probe(fake, 0, 1, 1, fake, 1024, None, None) == 5
-    assert B.lib.hlq_mfma_probe(fake, 4096, 0, 1, fake, 1024, None, None) == 3
-    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 0, fake, 1024, None, None) == 3
-    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 65537, fake, 1 << 30, None, None) == 3
-    assert B.lib.hlq_mfma_probe(fake, 4096, 1, 2, fake, 2047, None, None) == 4
+    assert B.lib.hlq_mfma_probe(0, None, 4096, 1, 1, fake, 1024, None, None) == 1
+    assert B.lib.hlq_mfma_probe(0, fake, 4096, 1, 1, None, 1024, None, None) == 1
+    assert B.lib.hlq_mfma_probe(0, fake + 8, 4096, 1, 1, fake, 1024, None, None) == 5
+    assert B.lib.hlq_mfma_probe(0, fake, 4100, 1, 1, fake, 1024, None, None) == 5
+    assert B.lib.hlq_mfma_probe(0, fake, 0, 1, 1, fake, 1024, None, None) == 5
+    assert B.lib.hlq_mfma_probe(0, fake, 4096, 0, 1, fake, 1024, None, None) == 3
+    assert B.lib.hlq_mfma_probe(0, fake, 4096, 1, 0, fake, 1024, None, None) == 3
+    assert B.lib.hlq_mfma_probe(0, fake, 4096, 1, 65537, fake, 1 << 30, None, None) == 3
+    assert B.lib.hlq_mfma_probe(0, fake, 4096, 1, 2, fake, 2047, None, None) == 4
+    assert B.lib.hlq_mfma_probe(2, fake, 4096, 1, 1, fake, 1024, None, None) == 3
+    assert B.lib.hlq_mfma_probe(-1, fake, 4096, 1, 1, fake, 1024, None, None) == 3
 
 
 def test_workspace_sizes_cover_every_path():

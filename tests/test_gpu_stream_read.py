@@ -77,3 +77,48 @@ def test_mfma_probe_sums_what_its_operands_say():
         b = [ksums(w, 2 * o + 1) for o in range(4)]
         want = iters * sum(float(a[(o + c) % 4] @ b[o]) for o in range(4) for c in range(4))
         assert got[w] == want, (w, got[w], want)
+
+
+def test_mx_probe_sums_what_its_operands_say():
+    # kind 1 (bf8 x fp4, 16x16x128): operands restricted to values whose products and sums are exact.  An 8-bit
+    # operand lane l holds row l % 16, k = 16 (l / 16) + i for its first 16 bytes and 64 + 16 (l / 16) + i for the
+    # next 16; a 4-bit operand lane holds column l % 16, k = 32 (l / 16) + n for nibble n of its 16 bytes.
+    iters, blocks = 2, 3
+    print("mfma_probe mx", iters, blocks, flush=True)
+    rng = np.random.default_rng(11)
+    waves = blocks * 4
+    units = waves * 12
+    a_codes = np.array([0x00, 0x38, 0x3C, 0x3E], dtype=np.uint8)          # bf8 e5m2: 0, 0.5, 1, 1.5
+    a_vals = np.array([0.0, 0.5, 1.0, 1.5])
+    b_codes = np.array([0x0, 0x2, 0x4, 0xA, 0x1], dtype=np.uint8)         # fp4 e2m1: 0, 1, 2, -1, 0.5
+    b_vals = np.array([0.0, 1.0, 2.0, -1.0, 0.5])
+    ai = rng.integers(0, 4, size=(units, 64, 16))
+    bi = rng.integers(0, 5, size=(units, 64, 32))
+    raw = a_codes[ai].copy()                                              # every unit as 8-bit operand bytes ...
+    for u in range(2, units, 3):                                          # ... and every third one as packed nibbles
+        nib = b_codes[bi[u]]
+        raw[u] = (nib[:, 0::2] | (nib[:, 1::2] << 4)).astype(np.uint8)
+    ops = torch.from_numpy(raw.reshape(-1).view(np.float16)).cuda()
+    sink = torch.zeros(blocks * 256, dtype=torch.float32, device="cuda")
+    flop = B.hlq_mfma_probe(ops, iters, blocks, sink, kind=1)
+    torch.cuda.synchronize()
+    assert flop == waves * iters * 32 * 2.0 * 16 * 16 * 128
+    got = sink.cpu().numpy().astype(np.float64).reshape(waves, 64).sum(axis=1)
+
+    def a_ksums(w, o):      # sum over the 16 rows, per k
+        lo, hi = a_vals[ai[w * 12 + 3 * o]], a_vals[ai[w * 12 + 3 * o + 1]]          # [lane, 16]
+        ks = np.zeros(128)
+        for kb in range(4):
+            ks[16 * kb:16 * kb + 16] = lo[16 * kb:16 * kb + 16].sum(axis=0)
+            ks[64 + 16 * kb:64 + 16 * kb + 16] = hi[16 * kb:16 * kb + 16].sum(axis=0)
+        return ks
+
+    def b_ksums(w, o):      # sum over the 16 columns, per k
+        v = b_vals[bi[w * 12 + 3 * o + 2]]                                            # [lane, 32]
+        return np.concatenate([v[16 * g:16 * g + 16].sum(axis=0) for g in range(4)])
+
+    for w in range(waves):
+        a = [a_ksums(w, o) for o in range(4)]
+        b = [b_ksums(w, o) for o in range(4)]
+        want = iters * sum(float(a[(o + c) % 4] @ b[o]) for o in range(4) for c in range(8))
+        assert got[w] == want, (w, got[w], want)
