@@ -230,14 +230,13 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
  *     for reference, not as a tuned competitor),
  * 1 = table lookups always,
  * 2 = matrix cores always: for a few rows (M <= 4 at G >= 128, <= 2 at G = 64, 1 at G = 32) the
- *     GEMV kernel of hlq_set_gemv_path(2) with several activation rows per operand, above that
- *     the tiled kernel that rebuilds W^ in fp16 registers (hlq_lut_gemm_batch keeps up to twice
- *     as many rows on the GEMV kernel, where one launch for several problems pays),
+ *     GEMV kernel of hlq_set_gemv_path(2) with several activation rows per operand, for 5..16 rows on large
+ *     problems (G >= 128) the many-rows kernel, otherwise the tiled kernel that rebuilds W^ in fp16 registers
+ *     (hlq_lut_gemm_batch keeps up to twice as many rows on the GEMV kernel at G <= 64),
  * 3 = as 2 but never the few-rows GEMV kernel,
- * 4 = as 2, and hlq_lut_gemm_batch keeps up to 16 rows (G >= 128) on the many-rows kernel whatever the size of
- *     the launch (by default it takes 5..8 rows always and 9..16 rows when the launch has at least 2400
- *     chunk-tiles of 64 columns x 128 k, e.g. two 4096 x 4096 matrices; smaller launches of 9..16 rows
- *     go to the tiled kernel).
+ * 4 = as 2, and 5..16 rows (G >= 128) always go to the many-rows kernel (by default only when the call or grouped
+ *     launch is large enough for it to win: from 4096 chunk-tiles of 64 columns x 128 k at q >= 3 and 12000 at
+ *     q <= 2 for up to 8 rows, from 2400 resp. 20000 for 9..16 rows; smaller ones go to the tiled kernel).
  * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel represents scales up to |s_j| < 512 (and
  * zeros of that size); it checks what it loads, and a call whose weights lie outside is computed again
  * by an fp32 kernel launched behind it (slow, but right for every finite fp16 parameter). */

@@ -298,6 +298,10 @@ hlq_status hlq_launch_gemm(const HlqDims &dm, const void *packed, const uint16_t
         // hardly depends on M up to 32 rows, is as fast or faster for a single call
         if (g_gemm_path.load(std::memory_order_relaxed) != 3 && M <= hlq_gemv_mx_rows_per_set(dm.G))
             return hlq_launch_gemm_mx_rows(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
+        // 5..16 rows on a large matrix: the many-rows kernel (same rule as for grouped launches)
+        if (g_gemm_path.load(std::memory_order_relaxed) != 3 && M <= hlq_gemm_rows_max(dm.G) &&
+            (hlq_gemm_rows_all() || hlq_gemm_rows_wins((long)dm.ntiles * dm.nchunks, dm.q, M)))
+            return hlq_launch_gemm_mx_rows(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
         return hlq_launch_gemm_mfma(dm, packed, X, M, ldx, Y, ldy, out, ws, st);
     }
     return hlq_launch_gemm_lut(dm, packed, X, M, ldx, Y, ldy, out, ws, st);

@@ -789,20 +789,33 @@ int hlq_gemm_mx_rows_per_pass(int G)
     return many > two_sets ? many : two_sets;
 }
 
+// Many-rows kernel or tiled kernel for 5..16 rows (G >= 128)?  Measured on 8B / 70B layer shapes, single calls and
+// grouped launches, in microseconds (many-rows against tiled).  The many-rows kernel pays per MFMA (q planes x four
+// activation terms per row, twice the instructions from 9 rows on) and needs a launch large enough to spread its
+// wavefronts; the tiled kernel pays for rebuilding the weights, whatever M.
+//   q = 4, up to 8 rows:  2048 chunk-tiles 15.1 / 12.3,  7168: 19.3 / 23.6 and 21.6 / 27.6,  28672: 41 / 64, 8B layer 40 / 68
+//   q = 4, 9..16 rows:    2048: 17.1 / 12.6,  2560 (two matrices) 18.1 / 19.6,  7168: 24.2 / 23.8 and 26.5 / 28.2,  8B layer 60 / 69
+//   q = 2, up to 8 rows:  2048: 13.9 / 10.5,  7168: 16.6 / 16.4 and 19.3 / 17.9,  28672: 29 / 41
+//   q = 2, 9..16 rows:    7168: 20.8 / 16.8 and 23.2 / 18.3,  28672: 43.4 / 42.5,  8B layer 47 / 49
+bool hlq_gemm_rows_wins(long units, int q, int64_t M)
+{
+    if (M <= 8) return units >= (q >= 3 ? 4096 : 12000);
+    return units >= (q >= 3 ? 2400 : 20000);
+}
+
 // Whether a grouped launch of M rows goes to the matrix-core GEMV-shaped kernels (few-rows / many-rows) rather
-// than to the tiled kernel.  Up to 8 rows always (where a pass carries them).  9..16 rows (four chained operands per
-// item in the many-rows kernel): measured on 8B-layer shapes at q = 2..4, the many-rows kernel wins once the launch
-// has a few thousand chunk-tiles (whole layer at q = 4: 60 against 69 us; two small problems: 18 against 20 us),
-// the tiled kernel on a single 4096 x 4096 (16 against 18 us); hlq_set_gemm_path(4) sends all of them here.
+// than to the tiled kernel: up to one row set (four rows at G >= 128) and whatever the second row set of the
+// GEMV kernel carries at G <= 64 always; 5..16 rows at G >= 128 by the rule above; hlq_set_gemm_path(4) sends all of
+// them here.
 bool hlq_gemm_batch_on_mx(int count, const HlqGemvItem *items, int64_t M)
 {
     if (count < 1 || M < 1) return false;
     const int G = items[0].dm.G;
     if (M > hlq_gemm_mx_rows_per_pass(G)) return false;
-    if (M <= 8 || hlq_gemm_rows_all()) return true;
+    if (M <= hlq_gemv_mx_rows_per_set(G) || hlq_gemm_rows_max(G) == 0 || hlq_gemm_rows_all()) return true;
     long units = 0;
     for (int i = 0; i < count; ++i) units += (long)items[i].dm.ntiles * items[i].dm.nchunks;
-    return units >= 2400;
+    return hlq_gemm_rows_wins(units, items[0].dm.q, M);
 }
 
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M)

@@ -159,6 +159,8 @@ hlq_status hlq_launch_gemm_safe(int count, const HlqGemvItem *items, int64_t M, 
 int hlq_gemv_mx_rows_per_set(int G);
 int hlq_gemm_mx_rows_per_pass(int G);
 bool hlq_gemm_batch_on_mx(int count, const HlqGemvItem *items, int64_t M);
+bool hlq_gemm_rows_wins(long units, int q, int64_t M);
+int hlq_gemm_rows_max(int G);
 bool hlq_gemm_uses_mx_rows(int64_t M);
 bool hlq_gemm_rows_all();
 size_t hlq_gemm_mx_partial_bytes(const HlqDims &dm, int64_t M);
