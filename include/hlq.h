@@ -170,11 +170,13 @@ HLQ_API hlq_status hlq_lut_gemv_batch(int count, const hlq_desc *descs, const vo
 /* Several independent products Y_i[M, N_i] = X_i[M, K_i] @ W^_i in one launch (the GEMMs of a
  * decoder layer: Sec. 2, batched rows).  All problems share q, G and M; X_i row-major with
  * leading dimension ldx[i] >= K_i (a multiple of 8 for M > 1), Y_i with ldy[i] >= N_i; descs,
- * packed, X, ldx, Y, ldy are host arrays of `count` (1..8) entries.  Up to what one pass of the
- * few-rows kernel carries (8 rows at G >= 128, 4 at G = 64, 2 at G = 32) that kernel takes all
- * problems; above it one launch of the tiled matrix-core kernel does (plus one that adds the
- * partial sums when K is cut: the seven GEMMs of an 8B layer run 1.3x faster than as seven calls
- * at M = 2048 and 2x faster at M = 16).  If the
+ * packed, X, ldx, Y, ldy are host arrays of `count` (1..8) entries.  One launch of the few-rows
+ * kernel takes all problems up to 4 rows at G >= 128 (4 at G = 64, 2 at G = 32: two row sets);
+ * 5..16 rows at G >= 128 go to the many-rows kernel (a small pre-pass that writes the activations in
+ * matrix-core operand form into the workspace, then one launch) when the launch is large enough
+ * for it to win, see hlq_set_gemm_path; everything else to one launch of the tiled matrix-core
+ * kernel (plus one that adds the partial sums when K is cut: the seven GEMMs of an 8B layer run
+ * 1.3x faster than as seven calls at M = 2048).  If the
  * lookup formulation is forced the problems run one after the other on the stream.  M = 0 is a
  * no-op.
  *   ws / ws_bytes: workspace of at least hlq_gemm_batch_workspace_bytes(count, descs, M). */
@@ -193,12 +195,12 @@ HLQ_API hlq_status hlq_lut_gemm_batch(int count, const hlq_desc *descs, const vo
  * Values outside the ranges above: HLQ_ERR_UNSUPPORTED. */
 HLQ_API hlq_status hlq_set_gemv_plan(int tiles_per_wave, int waves_per_workgroup, int chunks_per_wave);
 
-/* Host-only: the work split hlq_lut_gemv_batch (M = 1) or the few-rows launch of hlq_lut_gemm_batch
- * (2 <= M <= rows one pass carries) would use for these `count` problems with the knobs as they
+/* Host-only: the work split hlq_lut_gemv_batch (M = 1) or the few-rows / many-rows launch of
+ * hlq_lut_gemm_batch (2 <= M <= rows one pass carries: 16 at G >= 128, 4 at G = 64, 2 at G = 32) would use for these `count` problems with the knobs as they
  * are now; nothing is launched and no GPU is needed.  For tests and tools: every K slice of a
  * plan starts inside K, i.e. (slices - 1) * chunks_per_slice < K / 128.
  *   descs host array of `count` (1..8) descriptors sharing q and G; out host array of `count`.
- * M outside what the few-rows kernel carries: HLQ_ERR_UNSUPPORTED. */
+ * M outside that range: HLQ_ERR_UNSUPPORTED. */
 typedef struct {
     int32_t formulation;          /* 1 = table lookups, 2 = matrix cores                             */
     int32_t waves_per_workgroup;  /* wavefronts of a workgroup                                       */
