@@ -163,11 +163,11 @@ def test_config4_prefill_whole_layer_one_grouped_launch(M):
     torch.cuda.empty_cache()
 
 
-@pytest.mark.parametrize("M", [2, 5, 8, 16])
+@pytest.mark.parametrize("M", [1, 2, 4, 5, 8, 16])
 def test_config3_small_batch_whole_layer_one_grouped_launch(M):
     # configuration 3 in the launch the small-batch figures are quoted on: the seven matrices of the 8B layer,
-    # q = 4, in one hlq_lut_gemm_batch call (few-rows kernel with one and two row sets up to M = 8, tiled kernel
-    # above), every output column against the C oracle
+    # q = 4, in one hlq_lut_gemm_batch call with the default dispatch (few-rows kernel up to M = 4, many-rows
+    # kernel with two and four chained operands above), every output column against the C oracle
     from paper_2510_19482_amd import binding as B
     from gpu_util import dev
     q, G = 4, 128
