@@ -236,9 +236,11 @@ HLQ_API hlq_status hlq_set_gemv_path(int path);
  *     problems (G >= 128) the many-rows kernel, otherwise the tiled kernel that rebuilds W^ in fp16 registers
  *     (hlq_lut_gemm_batch keeps up to twice as many rows on the GEMV kernel at G <= 64),
  * 3 = as 2 but never the few-rows GEMV kernel,
- * 4 = as 2, and 5..16 rows (G >= 128) always go to the many-rows kernel (by default only when the call or grouped
+ * 4 = as 2, and 3..16 rows (G >= 128) always go to the many-rows kernel (by default only when the call or grouped
  *     launch is large enough for it to win: from 4096 chunk-tiles of 64 columns x 128 k at q >= 3 and 12000 at
- *     q <= 2 for up to 8 rows, from 2400 resp. 20000 for 9..16 rows; smaller ones go to the tiled kernel).
+ *     q <= 2 for 5..8 rows, from 2400 resp. 20000 for 9..16 rows, smaller ones going to the tiled kernel; 3 and 4
+ *     rows from 20000 chunk-tiles at q = 4, 4 rows from 40000 at q = 3 and 60000 at q <= 2, otherwise they stay
+ *     on the few-rows GEMV kernel).
  * Other values: HLQ_ERR_UNSUPPORTED.  The fp16-rebuild kernel represents scales up to |s_j| < 512 (and
  * zeros of that size); it checks what it loads, and a call whose weights lie outside is computed again
  * by an fp32 kernel launched behind it (slow, but right for every finite fp16 parameter). */

@@ -10,7 +10,10 @@
 // terms lie along the ACCUMULATION: operand o holds terms [o TPO, (o + 1) TPO) of 16 / TPO activation
 // rows, the NT = 4 / TPO matrix-core instructions of an item (plane j, block of 16 columns) chain
 // through their accumulator, and what comes out is the finished dot product of every row -- one scale
-// multiplication per (row, column, plane).  NT = 2 carries up to 8 rows, NT = 4 up to 16.
+// multiplication per (row, column, plane).  NT = 2 carries up to 8 rows, NT = 4 up to 16.  NT = 1 is the other
+// end: all four terms of up to 4 rows in one operand, one matrix-core instruction per item, the four terms of a
+// result in the four 16-lane groups, added by two cross-lane adds at the very end (the arrangement of the GEMV
+// kernel, but with the activations converted once per call by the pre-pass instead of once per column tile).
 //
 // Two kernels.  hlq_rows_split_kernel runs once per call: the workgroups of a (problem, activation row) find
 // the row's largest magnitude, which fixes a power-of-two scale that puts the row high in the bf8 range
@@ -154,7 +157,7 @@ __global__ void __launch_bounds__(512)
 hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_flag, const GemvProbs probs)
 {
     static_assert(G >= 128, "one quant segment per chunk");
-    static_assert(NT == 2 || NT == 4, "two or four chained operands");
+    static_assert(NT == 1 || NT == 2 || NT == 4, "one operand, or two or four chained ones");
     constexpr int TPO = 4 / NT;            // terms per operand
     constexpr int RPO = 16 / TPO;          // activation rows an operand carries
     constexpr int MSTR = rows_meta_stride(Q);
@@ -334,7 +337,7 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
 #pragma unroll
             for (int i = 0; i < 2 * NT; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, NT == 2 ? 6 : 3, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, NT == 1 ? 9 : NT == 2 ? 6 : 3, 0);
             }
             __builtin_amdgcn_sched_barrier(0);
             pA = dA; pB = dB; B0 = nB0; B1 = nB1;
@@ -365,12 +368,13 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
     float y[4][4];
 #pragma unroll
     for (int sl = 0; sl < 4; ++sl) {
-        const int row = (NT == 2 ? 4 * (g & 1) : 4 * g) + sl;
+        const int row = (NT == 1 ? 0 : NT == 2 ? 4 * (g & 1) : 4 * g) + sl;
         const float f = __builtin_bit_cast(float, (uint32_t)(127 + 2 - 29 + P.xexp[row]) << 23);   // 4 * 2^(e-29)
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
             float v = acc[sl][cb];
-            if (NT == 2) v += __shfl_xor(v, 32);   // lanes 32..63 hold terms 2, 3 of the same rows
+            if (NT == 1) v += __shfl_xor(v, 16);   // one term per 16-lane group
+            if (NT <= 2) v += __shfl_xor(v, 32);   // NT = 2: lanes 32..63 hold terms 2, 3 of the same rows
             y[sl][cb] = v * f;
         }
     }
@@ -390,8 +394,8 @@ hlq_gemm_rows_kernel(const int4v bb_lo, const int4v bb_hi, const int out_f32_fla
         }
     }
     if (!tile_ok || part != 0) return;
-    if (NT == 2 && g >= 2) return;
-    const int row0 = (NT == 2 ? 4 * (g & 1) : 4 * g);
+    if ((NT == 2 && g >= 2) || (NT == 1 && g >= 1)) return;
+    const int row0 = (NT == 1 ? 0 : NT == 2 ? 4 * (g & 1) : 4 * g);
     const size_t n0 = (size_t)tile * HLQ_TILE_N;
     const size_t ldy = (size_t)P.ldy;
     const int out_f32 = out_f32_flag;
@@ -467,7 +471,10 @@ void launch_qg(const GemvBatch &b, unsigned nblocks, int W, int rows, hipStream_
     const dim3 blk(64 * W);
     const GemvKernelArgs a = gemv_kernel_args(b);
     if constexpr (G >= 128) {
-        if (rows <= 8) {
+        if (rows <= 4) {
+            hlq_rows_split_kernel<1><<<dim3(4, b.count, 8), 256, 0, st>>>(a.probs);
+            hlq_gemm_rows_kernel<Q, G, 1><<<nblocks, blk, (size_t)rows_lds_bytes(Q, W), st>>>(a.lo, a.hi, a.out_f32, a.probs);
+        } else if (rows <= 8) {
             hlq_rows_split_kernel<2><<<dim3(8, b.count, 8), 256, 0, st>>>(a.probs);
             hlq_gemm_rows_kernel<Q, G, 2><<<nblocks, blk, (size_t)rows_lds_bytes(Q, W), st>>>(a.lo, a.hi, a.out_f32, a.probs);
         } else {
@@ -492,7 +499,7 @@ hlq_status launch_q(int G, const GemvBatch &b, unsigned nblocks, int W, int rows
 size_t hlq_gemm_rows_xt_bytes(const HlqDims &dm, int64_t M)
 {
     if (M < 1 || M > hlq_gemm_rows_max(dm.G)) return 0;
-    const size_t nt = M <= 8 ? 2 : 4;
+    const size_t nt = M <= 4 ? 1 : M <= 8 ? 2 : 4;
     return (size_t)dm.nchunks * nt * ROWS_OPERAND_BYTES + 256;   // operands + the row exponents, kept 256-byte aligned
 }
 

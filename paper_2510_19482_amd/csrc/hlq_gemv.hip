@@ -565,8 +565,13 @@ static hlq_status plan_gemv_batch(int count, const HlqGemvItem *items, hlq_out_d
     const bool mx = use_mx() || rows > 1;   // several activation rows exist in the matrix-core kernels only
     // more rows than one operand of the GEMV kernel holds: the many-rows kernel (terms chained through the
     // accumulator, activations converted once per workgroup), where it exists for this group size
-    const bool rowsk = rows > hlq_gemv_mx_rows_per_set(items[0].dm.G) && rows <= hlq_gemm_rows_max(items[0].dm.G) &&
-                       rows <= hlq_gemm_mx_rows_per_pass(items[0].dm.G);
+    bool rowsk = rows > hlq_gemv_mx_rows_per_set(items[0].dm.G) && rows <= hlq_gemm_rows_max(items[0].dm.G) &&
+                 rows <= hlq_gemm_mx_rows_per_pass(items[0].dm.G);
+    // three or four rows (which the GEMV kernel's one row set also holds): the one-operand instantiation of the
+    // many-rows kernel where its pre-pass pays
+    if (!rowsk && rows >= 3 && rows <= hlq_gemm_rows_max(items[0].dm.G) &&
+        (hlq_gemm_rows_all() || hlq_gemm_rows_wins_few(units, items[0].dm.q, rows)))
+        rowsk = true;
     if (rowsk) {
         pl.W = 4;
         // chunks per K slice: long enough that the partial sums (rows x columns x slices) stay a small part of the
@@ -797,6 +802,18 @@ int hlq_gemm_mx_rows_per_pass(int G)
 //   q = 4, 9..16 rows:    2048: 17.1 / 12.6,  2560 (two matrices) 18.1 / 19.6,  7168: 24.2 / 23.8 and 26.5 / 28.2,  8B layer 60 / 69
 //   q = 2, up to 8 rows:  2048: 13.9 / 10.5,  7168: 16.6 / 16.4 and 19.3 / 17.9,  28672: 29 / 41
 //   q = 2, 9..16 rows:    7168: 20.8 / 16.8 and 23.2 / 18.3,  28672: 43.4 / 42.5,  8B layer 47 / 49
+// The same question for 3 or 4 rows, where the alternative is the few-rows instantiation of the GEMV kernel
+// (which converts the activations in every wavefront and needs no pre-pass).  Measured, many-rows against few-rows:
+//   8B layer (27648 chunk-tiles)  q = 4: 33.3 / 36.4 (3 rows), 33.2 / 39.5 (4 rows);  q = 3: 28.8 / 27.0, 28.7 / 30.1;
+//                                 q = 2: 25.6 / 22.5, 26.0 / 26.0
+//   70B layer (104448), q = 2: 66.3 / 68.3, 67.0 / 77.6;   one 4096 x 14336 (7168), q = 4: 18.5 / 13.0, 18.5 / 14.3
+bool hlq_gemm_rows_wins_few(long units, int q, int rows)
+{
+    if (q >= 4) return units >= 20000;
+    if (rows < 4) return false;
+    return units >= (q == 3 ? 40000 : 60000);
+}
+
 bool hlq_gemm_rows_wins(long units, int q, int64_t M)
 {
     if (M <= 8) return units >= (q >= 3 ? 4096 : 12000);

@@ -160,6 +160,7 @@ int hlq_gemv_mx_rows_per_set(int G);
 int hlq_gemm_mx_rows_per_pass(int G);
 bool hlq_gemm_batch_on_mx(int count, const HlqGemvItem *items, int64_t M);
 bool hlq_gemm_rows_wins(long units, int q, int64_t M);
+bool hlq_gemm_rows_wins_few(long units, int q, int rows);
 int hlq_gemm_rows_max(int G);
 bool hlq_gemm_uses_mx_rows(int64_t M);
 bool hlq_gemm_rows_all();

@@ -1,4 +1,4 @@
-"""The many-rows kernel (5 <= M <= 16 rows at quant groups of 128 / 256, reached through
+"""The many-rows kernel (3 <= M <= 16 rows at quant groups of 128 / 256, reached through
 hlq_lut_gemm_batch): every row count, every plane count, ragged tiles, surplus wavefronts, K split
 across workgroups, strided X / Y, rows of very different magnitude, one-hot rows -- against the oracle."""
 import numpy as np
@@ -22,7 +22,7 @@ def say(*a):
 
 @pytest.fixture(autouse=True)
 def rows_kernel_for_all_row_counts():
-    # by default the many-rows kernel takes 5..8 rows and the tiled kernel the rest; here it gets all sixteen
+    # by default the many-rows kernel takes 5..16 rows of large launches only; here it gets everything from 3 rows up
     B.set_gemm_path(B.GEMM_ROWS16)
     yield
     B.set_gemm_path(B.GEMM_AUTO)
@@ -50,7 +50,7 @@ def run_batch(d, packed, X, out_f32=True, ldx=None, ldy=None):
     return Y.float().cpu().numpy().astype(np.float64)
 
 
-@pytest.mark.parametrize("M", list(range(5, 17)))
+@pytest.mark.parametrize("M", list(range(3, 17)))
 @pytest.mark.parametrize("q,G", [(4, 128), (2, 128), (3, 256), (1, 128)])
 def test_every_row_count(M, q, G):
     K, N = 2304, 1096            # 18 chunks (several K slices), 17 full tiles + an 8-column tail: three tile groups,
@@ -71,7 +71,7 @@ def test_every_row_count(M, q, G):
 
 
 @pytest.mark.parametrize("w,cpw", [(4, 1), (4, 2), (2, 3), (8, 1), (4, 6), (8, 18), (2, 64)])
-@pytest.mark.parametrize("M", [7, 13])
+@pytest.mark.parametrize("M", [4, 7, 13])
 def test_forced_work_splits(M, w, cpw):
     # wavefronts per workgroup and run lengths that cut K inside the workgroup, across workgroups, or both
     K, N, q, G = 2304, 520, 3, 128
@@ -84,7 +84,7 @@ def test_forced_work_splits(M, w, cpw):
     assert O.row_rel_err(run_batch(d, packed, X), O.gemm_dequant(X, codes, S, Z, q, G)).max() <= F32_TOL
 
 
-@pytest.mark.parametrize("M", [6, 16])
+@pytest.mark.parametrize("M", [3, 6, 16])
 def test_strided_rows(M):
     K, N, q, G = 1024, 200, 2, 128
     codes, S, Z = synth.make_weight(K, N, q, G, "rows-ld")
@@ -94,7 +94,7 @@ def test_strided_rows(M):
     assert O.row_rel_err(Y, O.gemm_dequant(X, codes, S, Z, q, G)).max() <= F32_TOL
 
 
-@pytest.mark.parametrize("M", [8, 12])
+@pytest.mark.parametrize("M", [4, 8, 12])
 def test_rows_of_very_different_magnitude(M):
     # each row has a power-of-two scale of its own: a row 2^15 times smaller than its neighbour keeps its precision
     K, N, q, G = 2048, 264, 4, 128
@@ -124,7 +124,7 @@ def test_zero_rows_and_zero_chunks():
     assert O.row_rel_err(Y[keep], ref[keep]).max() <= F32_TOL
 
 
-@pytest.mark.parametrize("M", [5, 16])
+@pytest.mark.parametrize("M", [3, 5, 16])
 def test_one_hot_rows_read_back_weights(M):
     # X[m] = e_k(m): Y[m] = W^[k(m), :]; catches any mix-up of rows, terms, k order or scales
     K, N, q, G = 1024, 200, 3, 128
